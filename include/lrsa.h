@@ -1,0 +1,136 @@
+/* lrsa.h -- C ABI of the MI355X (gfx950) hot path of Lag-Relative Sparse Attention (LRSA).
+ *
+ * The path, in the paper's notation (Method section): per attention head i the states
+ * Q_i, K_i, V_i in R^{n x d_h} (Eq. 1); the KV sequence is split into a sink of S tokens and
+ * chunks of the lag size L; each chunk p is scored against the chunk after it (Eq. 4-8); the
+ * top r*L = K tokens of every chunk survive (text after Eq. 8); attention (Eq. 2-3) runs under
+ * the chunked mask of the "Attention Filling" steps: a query sees the sink, the survivors of
+ * every chunk that lies more than `local_prev` chunks behind its own, the `local_prev` chunks
+ * before its own in full, and its own chunk causally.
+ *
+ * Conventions for every call
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library neither frees
+ *     nor keeps them after the call returns.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream);
+ *     the call returns without synchronising.
+ *   - `ws` is a caller-owned device scratch buffer of at least lrsa_workspace_bytes() bytes,
+ *     256-byte aligned; it may be NULL when that size is 0.  Its contents are undefined after
+ *     the call.  Calls that share one workspace must be ordered on one stream.
+ *   - Outputs are fully overwritten; they need not be initialised.
+ *   - Return value: LRSA_OK (0) or a negative lrsa_status.  Arguments are validated before
+ *     any HIP call, so argument errors are reported without touching the GPU.  The library
+ *     never aborts and throws nothing.  lrsa_last_error() describes the last failure of the
+ *     calling thread.
+ *   - NaN/Inf in the inputs give undefined results and are not checked.
+ *
+ * Partition (text after Eq. 8): P = floor((n-S)/L) full chunks C_p = [S+pL, S+(p+1)L), a tail
+ * of R = n-S-PL tokens that forms one more query chunk, nq = P + (R>0) query chunks, and
+ * Ns = max(nq-1-local_prev, 0) chunks that are ever seen compressed and therefore scored.
+ */
+#ifndef LRSA_H
+#define LRSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LRSA_OK = 0,
+    LRSA_ERR_INVALID_ARG = -1, /* null pointer, K > L, heads_q % heads_kv != 0, bad stride, small ws ... */
+    LRSA_ERR_UNSUPPORTED = -2, /* head_dim / dtype combination that is not built                         */
+    LRSA_ERR_HIP = -3          /* a HIP call failed; the message carries hipGetErrorString                */
+} lrsa_status;
+
+typedef enum { LRSA_F32 = 0, LRSA_BF16 = 1 } lrsa_dtype;
+
+/* Which kernels serve the attention calls. */
+typedef enum {
+    LRSA_IMPL_AUTO = 0,   /* bf16 with head_dim 128: MFMA kernels; everything else: generic kernels */
+    LRSA_IMPL_GENERIC = 1 /* force the plain fp32-arithmetic kernels (any supported dtype/head_dim)  */
+} lrsa_impl;
+
+typedef struct {
+    int32_t batch;         /* B >= 1                                                                 */
+    int32_t heads_q;       /* query heads; heads_q % heads_kv == 0, group size G = heads_q/heads_kv  */
+    int32_t heads_kv;      /* KV heads; scores and the selection are per KV head                     */
+    int32_t seq;           /* n >= 1                                                                 */
+    int32_t head_dim;      /* d_h: 64 or 128                                                         */
+    int32_t sink;          /* S >= 0                                                                 */
+    int32_t lag;           /* L >= 2: lag = chunk size                                               */
+    int32_t topk;          /* K = r*L survivors per chunk, 1 <= K <= L                               */
+    int32_t std_ddof;      /* divisor of Std in Eq. 7 is d_h - std_ddof; 0 or 1 (the paper is silent, 1 is the default reading) */
+    int32_t local_prev;    /* chunks kept in full before the query's own chunk, >= 1; 1 is the paper's sliding window */
+    float softmax_scale;   /* <= 0 selects 1/sqrt(d_h) of Eq. 3                                      */
+    int32_t dtype;         /* lrsa_dtype of Q, K, V, O, dO, dQ, dK, dV                               */
+    int32_t impl;          /* lrsa_impl                                                              */
+    int64_t q_stride[3];   /* element strides of (batch, head, position) for Q, O, dO, dQ            */
+    int64_t kv_stride[3];  /* element strides of (batch, head, position) for K, V, dK, dV            */
+                           /* the channel stride is 1; position stride >= head_dim; rows 16-byte aligned */
+} lrsa_params;
+
+/* Which call a workspace size is asked for. */
+typedef enum { LRSA_WS_SCORE = 0, LRSA_WS_SELECT = 1, LRSA_WS_ATTN_FWD = 2, LRSA_WS_ATTN_BWD = 3 } lrsa_ws_kind;
+
+/* Ns of the partition above; pure host arithmetic.  Returns a negative lrsa_status on bad params. */
+int lrsa_num_scored_chunks(const lrsa_params *p);
+
+/* Bytes of device scratch the call `which` (lrsa_ws_kind) needs for these params; host arithmetic.
+ * Returns 0 for bad params (the call itself then reports the error). */
+size_t lrsa_workspace_bytes(const lrsa_params *p, int which);
+
+/* LagKV score, Eq. 4-8.  For Z in {K, V}, every (b, KV head h, chunk p < Ns): per-channel min and
+ * max over the rows of chunk p+1 (Eq. 4-5); rows of chunk p normalised with them (Eq. 6; a channel
+ * with max == min is divided by 1); Std over the d_h channels of each row, then Softmax over the L
+ * rows of the chunk (Eq. 7); score = score(K) + score(V) (Eq. 8).  fp32 arithmetic on the stored
+ * values.
+ *   K, V  : [B, Hkv, n, d_h] by kv_stride, dtype `dtype`                       (device, read)
+ *   score : [B, Hkv, Ns, L] fp32, contiguous                                    (device, written)
+ * Ns == 0 is legal: nothing is written and score may be NULL. */
+int lrsa_score(const lrsa_params *p, const void *K, const void *V, float *score,
+               void *ws, size_t ws_bytes, void *stream);
+
+/* Top-K per head and lag window (text after Eq. 8): for every (b, h, p) the K positions of chunk p
+ * with the largest score; equal scores go to the lowest position.
+ *   score : [B, Hkv, Ns, L] fp32, contiguous, every value > 0                   (device, read)
+ *   idx   : [B, Hkv, Ns, K] int32, contiguous; absolute positions in
+ *           [S+pL, S+(p+1)L), strictly ascending                                (device, written)
+ * Ns == 0 is legal: nothing is written and both pointers may be NULL. */
+int lrsa_select(const lrsa_params *p, const float *score, int32_t *idx,
+                void *ws, size_t ws_bytes, void *stream);
+
+/* Attention forward, Eq. 2-3 under the chunked mask: O[t] = sum_u softmax_u(scale q_t.k_u) v_u over
+ * the keys u <= t that are in the sink, in the local window of t's chunk, or listed in idx;
+ * lse[t] = log sum_u exp(scale q_t.k_u).  Query head hq reads KV head hq / G.
+ *   Q     : [B, Hq, n, d_h] by q_stride; K, V: [B, Hkv, n, d_h] by kv_stride    (device, read)
+ *   idx   : [B, Hkv, Ns, K] int32 as written by lrsa_select (ascending per chunk, inside the
+ *           chunk); may be NULL when Ns == 0                                     (device, read)
+ *   O     : [B, Hq, n, d_h] by q_stride, dtype `dtype`                           (device, written)
+ *   lse   : [B, Hq, n] fp32, contiguous                                          (device, written)
+ * idx is an input, so any valid selection (for instance one computed elsewhere) can be used. */
+int lrsa_attn_fwd(const lrsa_params *p, const void *Q, const void *K, const void *V, const int32_t *idx,
+                  void *O, float *lse, void *ws, size_t ws_bytes, void *stream);
+
+/* Attention backward: gradients of sum(O * dO) with the mask held constant (the selection carries
+ * no gradient).  With A = exp(scale Q K^T + M - lse): dV = A^T dO, dA = dO V^T,
+ * D = rowsum(dO * O), dS = A * (dA - D), dQ = scale dS K, dK = scale dS^T Q; dK and dV are summed
+ * over the G query heads of a group.
+ *   Q, K, V, idx as in lrsa_attn_fwd; O, lse as written by it; dO like O        (device, read)
+ *   dQ    : like Q; dK, dV: like K                                               (device, written)
+ */
+int lrsa_attn_bwd(const lrsa_params *p, const void *Q, const void *K, const void *V, const void *O,
+                  const void *dO, const float *lse, const int32_t *idx,
+                  void *dQ, void *dK, void *dV, void *ws, size_t ws_bytes, void *stream);
+
+/* Message of the calling thread's last failed call (static thread-local storage, never NULL). */
+const char *lrsa_last_error(void);
+
+/* ABI revision of this header; bumped when a signature or the struct changes. */
+int lrsa_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LRSA_H */

@@ -1,0 +1,7 @@
+"""MI355X-native hot path of Lag-Relative Sparse Attention: LagKV scoring, per-head top-K
+selection and block-sparse causal attention forward/backward, as HIP kernels for gfx950 behind
+the C ABI of include/lrsa.h.  This package holds the kernels' sources (csrc/), the build step
+and a ctypes binding; `inputs` is the seeded synthetic-input generator."""
+from . import inputs  # noqa: F401
+from .binding import (IMPL_AUTO, IMPL_GENERIC, LrsaError, LrsaParams, lib, lrsa_attn_bwd, lrsa_attn_fwd,  # noqa: F401
+                      lrsa_score, lrsa_select, make_params, num_scored_chunks, params_for, workspace_bytes)

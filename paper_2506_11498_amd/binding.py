@@ -1,0 +1,166 @@
+"""Thin ctypes binding of liblrsa.so: argument marshalling only.
+
+Every step of the path (score, select, attention forward and backward) runs in the HIP
+kernels behind the C ABI declared in include/lrsa.h; torch is used here for device memory
+and the current stream, nothing else.  There is no CPU fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblrsa.so")
+
+LRSA_F32, LRSA_BF16 = 0, 1
+IMPL_AUTO, IMPL_GENERIC = 0, 1
+WS_SCORE, WS_SELECT, WS_ATTN_FWD, WS_ATTN_BWD = 0, 1, 2, 3
+
+EXPORTS = ("lrsa_abi_version", "lrsa_last_error", "lrsa_num_scored_chunks", "lrsa_workspace_bytes",
+           "lrsa_score", "lrsa_select", "lrsa_attn_fwd", "lrsa_attn_bwd")
+
+
+class LrsaParams(ctypes.Structure):
+    """Mirror of lrsa_params in include/lrsa.h."""
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("heads_q", ctypes.c_int32), ("heads_kv", ctypes.c_int32),
+        ("seq", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("sink", ctypes.c_int32), ("lag", ctypes.c_int32), ("topk", ctypes.c_int32),
+        ("std_ddof", ctypes.c_int32), ("local_prev", ctypes.c_int32),
+        ("softmax_scale", ctypes.c_float), ("dtype", ctypes.c_int32), ("impl", ctypes.c_int32),
+        ("q_stride", ctypes.c_int64 * 3), ("kv_stride", ctypes.c_int64 * 3),
+    ]
+
+
+class LrsaError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"liblrsa error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load liblrsa.so (built in-tree by paper_2506_11498_amd.build); fail loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_2506_11498_amd.build` "
+                                    "(or __graft_entry__.build()).  There is no fallback path.")
+        L = ctypes.CDLL(LIB_PATH)
+        L.lrsa_last_error.restype = ctypes.c_char_p
+        L.lrsa_workspace_bytes.restype = ctypes.c_size_t
+        L.lrsa_workspace_bytes.argtypes = [ctypes.c_void_p, ctypes.c_int]
+        L.lrsa_num_scored_chunks.argtypes = [ctypes.c_void_p]
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        L.lrsa_score.argtypes = [vp, vp, vp, vp, vp, sz, vp]
+        L.lrsa_select.argtypes = [vp, vp, vp, vp, sz, vp]
+        L.lrsa_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.lrsa_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc < 0:
+        raise LrsaError(rc, lib().lrsa_last_error().decode())
+    return rc
+
+
+def make_params(q_shape, kv_shape, q_stride, kv_stride, *, sink: int, lag: int, topk: int, dtype,
+                std_ddof: int = 1, local_prev: int = 1, softmax_scale: float = 0.0,
+                impl: int = IMPL_AUTO) -> LrsaParams:
+    """Build lrsa_params from [B,H,n,d] shapes and element strides (the last stride must be 1)."""
+    B, Hq, n, d = q_shape
+    if q_stride[3] != 1 or kv_stride[3] != 1:
+        raise ValueError("the channel stride must be 1")
+    p = LrsaParams()
+    p.batch, p.heads_q, p.heads_kv, p.seq, p.head_dim = B, Hq, kv_shape[1], n, d
+    p.sink, p.lag, p.topk, p.std_ddof, p.local_prev = sink, lag, topk, std_ddof, local_prev
+    p.softmax_scale = softmax_scale
+    p.dtype = LRSA_F32 if dtype == torch.float32 else LRSA_BF16 if dtype == torch.bfloat16 else -1
+    p.impl = impl
+    for i in range(3):
+        p.q_stride[i] = q_stride[i]
+        p.kv_stride[i] = kv_stride[i]
+    return p
+
+
+def params_for(Q: torch.Tensor, K: torch.Tensor, **kw) -> LrsaParams:
+    return make_params(tuple(Q.shape), tuple(K.shape), Q.stride(), K.stride(), dtype=Q.dtype, **kw)
+
+
+def num_scored_chunks(p: LrsaParams) -> int:
+    return _check(lib().lrsa_num_scored_chunks(ctypes.byref(p)))
+
+
+def workspace_bytes(p: LrsaParams, which: int) -> int:
+    return int(lib().lrsa_workspace_bytes(ctypes.byref(p), which))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _workspace(p: LrsaParams, which: int, device, ws: Optional[torch.Tensor]) -> Tuple[Optional[torch.Tensor], int]:
+    need = workspace_bytes(p, which)
+    if need == 0:
+        return None, 0
+    if ws is None:
+        ws = torch.empty(need, dtype=torch.uint8, device=device)
+    return ws, ws.numel() * ws.element_size()
+
+
+def lrsa_score(p: LrsaParams, K: torch.Tensor, V: torch.Tensor, score: Optional[torch.Tensor] = None,
+               ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """LagKV scores [B, Hkv, Ns, L] fp32 (Eq. 4-8)."""
+    Ns = num_scored_chunks(p)
+    if score is None:
+        score = torch.empty((p.batch, p.heads_kv, Ns, p.lag), dtype=torch.float32, device=K.device)
+    ws, nb = _workspace(p, WS_SCORE, K.device, ws)
+    _check(lib().lrsa_score(ctypes.byref(p), _ptr(K), _ptr(V), _ptr(score), _ptr(ws), nb, _stream()))
+    return score
+
+
+def lrsa_select(p: LrsaParams, score: torch.Tensor, idx: Optional[torch.Tensor] = None,
+                ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Top-K positions per (batch, KV head, chunk): int32 [B, Hkv, Ns, K], ascending."""
+    Ns = num_scored_chunks(p)
+    if idx is None:
+        idx = torch.empty((p.batch, p.heads_kv, Ns, p.topk), dtype=torch.int32, device=score.device)
+    ws, nb = _workspace(p, WS_SELECT, score.device, ws)
+    _check(lib().lrsa_select(ctypes.byref(p), _ptr(score), _ptr(idx), _ptr(ws), nb, _stream()))
+    return idx
+
+
+def lrsa_attn_fwd(p: LrsaParams, Q, K, V, idx, O: Optional[torch.Tensor] = None,
+                  lse: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """Sparse attention forward: returns (O like Q, lse [B, Hq, n] fp32)."""
+    if O is None:
+        O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    if lse is None:
+        lse = torch.empty((p.batch, p.heads_q, p.seq), dtype=torch.float32, device=Q.device)
+    ws, nb = _workspace(p, WS_ATTN_FWD, Q.device, ws)
+    _check(lib().lrsa_attn_fwd(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(O), _ptr(lse),
+                               _ptr(ws), nb, _stream()))
+    return O, lse
+
+
+def lrsa_attn_bwd(p: LrsaParams, Q, K, V, O, dO, lse, idx, dQ=None, dK=None, dV=None,
+                  ws: Optional[torch.Tensor] = None):
+    """Sparse attention backward: returns (dQ like Q, dK like K, dV like V)."""
+    dQ = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device) if dQ is None else dQ
+    dK = torch.empty_strided(K.shape, K.stride(), dtype=K.dtype, device=K.device) if dK is None else dK
+    dV = torch.empty_strided(K.shape, K.stride(), dtype=K.dtype, device=K.device) if dV is None else dV
+    ws, nb = _workspace(p, WS_ATTN_BWD, Q.device, ws)
+    _check(lib().lrsa_attn_bwd(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(lse), _ptr(idx),
+                               _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ws), nb, _stream()))
+    return dQ, dK, dV

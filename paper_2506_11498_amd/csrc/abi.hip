@@ -1,0 +1,174 @@
+// C-ABI entry points of liblrsa: argument validation (before any HIP call), derived partition,
+// and dispatch to the kernel launchers.  Declarations and contracts are in include/lrsa.h.
+#include "../../include/lrsa.h"
+#include "common.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+// Validates the params and fills the derived dimensions.  Touches no HIP API.
+int make_dims(const lrsa_params* p, lrsa::Dims* D) {
+    if (!p) return fail(LRSA_ERR_INVALID_ARG, "params is NULL");
+    if (p->batch < 1 || p->heads_q < 1 || p->heads_kv < 1 || p->seq < 1)
+        return fail(LRSA_ERR_INVALID_ARG, "batch, heads_q, heads_kv and seq must be >= 1");
+    if (p->heads_q % p->heads_kv != 0)
+        return fail(LRSA_ERR_INVALID_ARG, "heads_q (%d) is not a multiple of heads_kv (%d)", p->heads_q, p->heads_kv);
+    if (p->sink < 0) return fail(LRSA_ERR_INVALID_ARG, "sink must be >= 0");
+    if (p->lag < 2) return fail(LRSA_ERR_INVALID_ARG, "lag must be >= 2");
+    if (p->topk < 1 || p->topk > p->lag)
+        return fail(LRSA_ERR_INVALID_ARG, "topk (%d) must be in [1, lag=%d]", p->topk, p->lag);
+    if (p->std_ddof != 0 && p->std_ddof != 1) return fail(LRSA_ERR_INVALID_ARG, "std_ddof must be 0 or 1");
+    if (p->local_prev < 1)
+        return fail(LRSA_ERR_INVALID_ARG, "local_prev must be >= 1 (0 would let a query use a selection made from later tokens)");
+    if (p->dtype != LRSA_F32 && p->dtype != LRSA_BF16) return fail(LRSA_ERR_UNSUPPORTED, "dtype %d is not built", p->dtype);
+    if (p->head_dim != 64 && p->head_dim != 128)
+        return fail(LRSA_ERR_UNSUPPORTED, "head_dim %d is not built (64 and 128 are)", p->head_dim);
+    if (p->impl != LRSA_IMPL_AUTO && p->impl != LRSA_IMPL_GENERIC) return fail(LRSA_ERR_INVALID_ARG, "unknown impl %d", p->impl);
+    if (!(p->softmax_scale == p->softmax_scale) || std::isinf(p->softmax_scale))
+        return fail(LRSA_ERR_INVALID_ARG, "softmax_scale is not finite");
+    const int vec = p->dtype == LRSA_F32 ? 4 : 8;  // elements per 16 bytes
+    const int64_t* strides[2] = {p->q_stride, p->kv_stride};
+    for (int s = 0; s < 2; ++s) {
+        const int64_t* st = strides[s];
+        if (st[2] < p->head_dim) return fail(LRSA_ERR_INVALID_ARG, "%s position stride %lld < head_dim", s ? "kv" : "q", (long long)st[2]);
+        for (int i = 0; i < 3; ++i) {
+            if (st[i] < 0) return fail(LRSA_ERR_INVALID_ARG, "negative stride");
+            if (st[i] % vec != 0) return fail(LRSA_ERR_INVALID_ARG, "%s stride %lld breaks 16-byte row alignment", s ? "kv" : "q", (long long)st[i]);
+        }
+    }
+    if ((int64_t)p->seq * p->heads_q > (int64_t)1 << 40) return fail(LRSA_ERR_INVALID_ARG, "problem too large");
+
+    D->B = p->batch; D->Hq = p->heads_q; D->Hkv = p->heads_kv; D->G = p->heads_q / p->heads_kv;
+    D->n = p->seq; D->d = p->head_dim; D->S = p->sink; D->L = p->lag; D->K = p->topk;
+    D->ddof = p->std_ddof; D->lp = p->local_prev;
+    const int64_t rest = p->seq > p->sink ? (int64_t)p->seq - p->sink : 0;
+    D->P = (int)(rest / p->lag);
+    D->R = (int)(rest - (int64_t)D->P * p->lag);
+    D->nq = D->P + (D->R > 0 ? 1 : 0);
+    D->Ns = D->nq - 1 - D->lp > 0 ? D->nq - 1 - D->lp : 0;
+    D->scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / std::sqrt((float)p->head_dim);
+    D->dtype = p->dtype;
+    for (int i = 0; i < 3; ++i) { D->qs[i] = p->q_stride[i]; D->ks[i] = p->kv_stride[i]; }
+    if (p->batch * (int64_t)p->heads_kv * 2 > 65535 || p->heads_q > 65535 || D->Ns > 65535)
+        return fail(LRSA_ERR_UNSUPPORTED, "batch*heads or chunk count beyond the launch grid limits");
+    return LRSA_OK;
+}
+
+bool use_mfma(const lrsa_params* p, const lrsa::Dims& D) { return p->impl == LRSA_IMPL_AUTO && lrsa::mfma_supported(D); }
+
+size_t ws_need(const lrsa_params* p, const lrsa::Dims& D, int which) {
+    switch (which) {
+        case LRSA_WS_SCORE: return lrsa::score_ws_bytes(D);
+        case LRSA_WS_SELECT: return lrsa::select_ws_bytes(D);
+        case LRSA_WS_ATTN_FWD: return use_mfma(p, D) ? lrsa::attn_fwd_mfma_ws_bytes(D) : lrsa::attn_fwd_generic_ws_bytes(D);
+        case LRSA_WS_ATTN_BWD: return use_mfma(p, D) ? lrsa::attn_bwd_mfma_ws_bytes(D) : lrsa::attn_bwd_generic_ws_bytes(D);
+        default: return 0;
+    }
+}
+
+int check_ws(const lrsa_params* p, const lrsa::Dims& D, int which, const void* ws, size_t ws_bytes) {
+    const size_t need = ws_need(p, D, which);
+    if (need == 0) return LRSA_OK;
+    if (!ws) return fail(LRSA_ERR_INVALID_ARG, "workspace is NULL but %zu bytes are needed", need);
+    if (ws_bytes < need) return fail(LRSA_ERR_INVALID_ARG, "workspace has %zu bytes, %zu are needed", ws_bytes, need);
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return fail(LRSA_ERR_INVALID_ARG, "workspace is not 256-byte aligned");
+    return LRSA_OK;
+}
+
+int hip_result(hipError_t e, const char* what) {
+    if (e == hipSuccess) return LRSA_OK;
+    return fail(LRSA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool misaligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 != 0; }
+
+}  // namespace
+
+extern "C" {
+
+int lrsa_abi_version(void) { return 1; }
+
+const char* lrsa_last_error(void) { return g_err; }
+
+int lrsa_num_scored_chunks(const lrsa_params* p) {
+    lrsa::Dims D;
+    const int rc = make_dims(p, &D);
+    return rc != LRSA_OK ? rc : D.Ns;
+}
+
+size_t lrsa_workspace_bytes(const lrsa_params* p, int which) {
+    lrsa::Dims D;
+    if (make_dims(p, &D) != LRSA_OK) return 0;
+    return ws_need(p, D, which);
+}
+
+int lrsa_score(const lrsa_params* p, const void* K, const void* V, float* score, void* ws, size_t ws_bytes,
+               void* stream) {
+    lrsa::Dims D;
+    int rc = make_dims(p, &D);
+    if (rc != LRSA_OK) return rc;
+    if (D.Ns == 0) return LRSA_OK;
+    if (!K || !V || !score) return fail(LRSA_ERR_INVALID_ARG, "lrsa_score: K, V and score must not be NULL");
+    if (misaligned16(K) || misaligned16(V)) return fail(LRSA_ERR_INVALID_ARG, "lrsa_score: K and V must be 16-byte aligned");
+    if ((rc = check_ws(p, D, LRSA_WS_SCORE, ws, ws_bytes)) != LRSA_OK) return rc;
+    return hip_result(lrsa::launch_score(D, K, V, score, ws, (hipStream_t)stream), "lrsa_score");
+}
+
+int lrsa_select(const lrsa_params* p, const float* score, int32_t* idx, void* ws, size_t ws_bytes, void* stream) {
+    lrsa::Dims D;
+    int rc = make_dims(p, &D);
+    if (rc != LRSA_OK) return rc;
+    if (D.Ns == 0) return LRSA_OK;
+    if (!score || !idx) return fail(LRSA_ERR_INVALID_ARG, "lrsa_select: score and idx must not be NULL");
+    if ((rc = check_ws(p, D, LRSA_WS_SELECT, ws, ws_bytes)) != LRSA_OK) return rc;
+    return hip_result(lrsa::launch_select(D, score, idx, ws, (hipStream_t)stream), "lrsa_select");
+}
+
+int lrsa_attn_fwd(const lrsa_params* p, const void* Q, const void* K, const void* V, const int32_t* idx, void* O,
+                  float* lse, void* ws, size_t ws_bytes, void* stream) {
+    lrsa::Dims D;
+    int rc = make_dims(p, &D);
+    if (rc != LRSA_OK) return rc;
+    if (!Q || !K || !V || !O || !lse) return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_fwd: Q, K, V, O and lse must not be NULL");
+    if (D.Ns > 0 && !idx) return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_fwd: idx is NULL but %d chunks are compressed", D.Ns);
+    if (misaligned16(Q) || misaligned16(K) || misaligned16(V) || misaligned16(O))
+        return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_fwd: tensors must be 16-byte aligned");
+    if ((rc = check_ws(p, D, LRSA_WS_ATTN_FWD, ws, ws_bytes)) != LRSA_OK) return rc;
+    const hipError_t e = use_mfma(p, D) ? lrsa::launch_attn_fwd_mfma(D, Q, K, V, idx, O, lse, ws, (hipStream_t)stream)
+                                        : lrsa::launch_attn_fwd_generic(D, Q, K, V, idx, O, lse, ws, (hipStream_t)stream);
+    return hip_result(e, "lrsa_attn_fwd");
+}
+
+int lrsa_attn_bwd(const lrsa_params* p, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                  const float* lse, const int32_t* idx, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes,
+                  void* stream) {
+    lrsa::Dims D;
+    int rc = make_dims(p, &D);
+    if (rc != LRSA_OK) return rc;
+    if (!Q || !K || !V || !O || !dO || !lse || !dQ || !dK || !dV)
+        return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_bwd: tensor pointers must not be NULL");
+    if (D.Ns > 0 && !idx) return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_bwd: idx is NULL but %d chunks are compressed", D.Ns);
+    if (misaligned16(Q) || misaligned16(K) || misaligned16(V) || misaligned16(O) || misaligned16(dO) ||
+        misaligned16(dQ) || misaligned16(dK) || misaligned16(dV))
+        return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_bwd: tensors must be 16-byte aligned");
+    if ((rc = check_ws(p, D, LRSA_WS_ATTN_BWD, ws, ws_bytes)) != LRSA_OK) return rc;
+    const hipError_t e =
+        use_mfma(p, D) ? lrsa::launch_attn_bwd_mfma(D, Q, K, V, O, dO, lse, idx, dQ, dK, dV, ws, (hipStream_t)stream)
+                       : lrsa::launch_attn_bwd_generic(D, Q, K, V, O, dO, lse, idx, dQ, dK, dV, ws, (hipStream_t)stream);
+    return hip_result(e, "lrsa_attn_bwd");
+}
+
+}  // extern "C"

@@ -1,0 +1,189 @@
+// LagKV scoring kernels (Eq. 4-8 of the paper) for gfx950.
+//
+// Three launches on one stream:
+//   k_minmax   per-channel min / max over a slice of the rows of the reference chunk p+1 (Eq. 4-5)
+//   k_sigma    rows of chunk p normalised by the combined min / max (Eq. 6), Std over channels
+//   k_softmax  Softmax over the L tokens of the chunk for K and for V, summed (Eq. 7-8)
+// All arithmetic is fp32 on the stored values with IEEE division and square root, two-pass
+// variance, max-subtracted softmax.  Rows are read with 16-byte loads, a row being spread over
+// consecutive lanes so that a wave reads whole rows back to back.
+#include "common.h"
+
+namespace lrsa {
+
+constexpr int SCORE_THREADS = 256;
+
+// rows of the chunk handled by one workgroup of k_minmax / k_sigma
+__host__ __device__ inline int score_rows_per_wg(int L) { return L < 256 ? L : 256; }
+__host__ __device__ inline int score_splits(int L) { int r = score_rows_per_wg(L); return (L + r - 1) / r; }
+
+// workspace layout: mm[unit][split][2][d] floats, then sigma[unit][L] floats; unit = ((b*Hkv+h)*2+z)*Ns+p
+struct ScoreWs {
+    float* mm;
+    float* sigma;
+};
+static inline size_t mm_floats(const Dims& D) { return size_t(D.B) * D.Hkv * 2 * D.Ns * score_splits(D.L) * 2 * D.d; }
+static inline size_t sigma_floats(const Dims& D) { return size_t(D.B) * D.Hkv * 2 * D.Ns * D.L; }
+
+size_t score_ws_bytes(const Dims& D) {
+    if (D.Ns == 0) return 0;
+    return align256(mm_floats(D) * 4) + align256(sigma_floats(D) * 4);
+}
+
+template <typename T>
+__global__ __launch_bounds__(SCORE_THREADS) void k_minmax(Dims D, const T* __restrict__ Kp, const T* __restrict__ Vp,
+                                                           float* __restrict__ mm) {
+    constexpr int VEC = Elem<T>::VEC;
+    const int lpr = D.d / VEC;               // lanes per row
+    const int rpp = SCORE_THREADS / lpr;     // rows per pass
+    const int split = blockIdx.x, p = blockIdx.y;
+    const int z = blockIdx.z & 1, bh = blockIdx.z >> 1;
+    const int b = bh / D.Hkv, h = bh % D.Hkv;
+    const T* Z = (z ? Vp : Kp) + b * D.ks[0] + h * D.ks[1];
+    const int rows_wg = score_rows_per_wg(D.L);
+    const int r0 = split * rows_wg;
+    const int r1 = min(r0 + rows_wg, D.L);
+    const int64_t base = int64_t(D.S) + int64_t(p + 1) * D.L;   // first row of the reference chunk
+    const int lane = threadIdx.x % lpr, rg = threadIdx.x / lpr;
+
+    float mn[VEC], mx[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) { mn[i] = INFINITY; mx[i] = -INFINITY; }
+    for (int r = r0 + rg; r < r1; r += rpp) {
+        float v[VEC];
+        Elem<T>::load(Z + (base + r) * D.ks[2] + lane * VEC, v);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { mn[i] = fminf(mn[i], v[i]); mx[i] = fmaxf(mx[i], v[i]); }
+    }
+    __shared__ float smn[SCORE_THREADS * 8], smx[SCORE_THREADS * 8];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        smn[(rg * lpr + lane) * VEC + i] = mn[i];
+        smx[(rg * lpr + lane) * VEC + i] = mx[i];
+    }
+    __syncthreads();
+    if (threadIdx.x < D.d) {
+        const int c = threadIdx.x;
+        float a = INFINITY, bmax = -INFINITY;
+        for (int g = 0; g < rpp; ++g) {
+            a = fminf(a, smn[g * D.d + c]);
+            bmax = fmaxf(bmax, smx[g * D.d + c]);
+        }
+        const int64_t unit = (int64_t(bh) * 2 + z) * D.Ns + p;
+        float* out = mm + (unit * gridDim.x + split) * 2 * D.d;
+        out[c] = a;
+        out[D.d + c] = bmax;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(SCORE_THREADS) void k_sigma(Dims D, const T* __restrict__ Kp, const T* __restrict__ Vp,
+                                                          const float* __restrict__ mm, float* __restrict__ sigma) {
+    constexpr int VEC = Elem<T>::VEC;
+    const int lpr = D.d / VEC;
+    const int rpp = SCORE_THREADS / lpr;
+    const int split = blockIdx.x, p = blockIdx.y;
+    const int z = blockIdx.z & 1, bh = blockIdx.z >> 1;
+    const int b = bh / D.Hkv, h = bh % D.Hkv;
+    const T* Z = (z ? Vp : Kp) + b * D.ks[0] + h * D.ks[1];
+    const int rows_wg = score_rows_per_wg(D.L);
+    const int nsplit = gridDim.x;
+    const int r0 = split * rows_wg;
+    const int r1 = min(r0 + rows_wg, D.L);
+    const int64_t base = int64_t(D.S) + int64_t(p) * D.L;       // first row of the scored chunk
+    const int lane = threadIdx.x % lpr, rg = threadIdx.x / lpr;
+    const int64_t unit = (int64_t(bh) * 2 + z) * D.Ns + p;
+
+    // combine the partial min / max of the reference chunk for this thread's channels
+    float mn[VEC], den[VEC];
+    {
+        const float* src = mm + unit * nsplit * 2 * D.d;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            const int c = lane * VEC + i;
+            float a = INFINITY, m = -INFINITY;
+            for (int s = 0; s < nsplit; ++s) {
+                a = fminf(a, src[s * 2 * D.d + c]);
+                m = fmaxf(m, src[s * 2 * D.d + D.d + c]);
+            }
+            mn[i] = a;
+            const float dd = m - a;
+            den[i] = dd == 0.0f ? 1.0f : dd;
+        }
+    }
+    // the lanes of one row leave the loop together, so the shuffles below stay among active lanes
+    for (int r = r0 + rg; r < r1; r += rpp) {
+        float v[VEC];
+        Elem<T>::load(Z + (base + r) * D.ks[2] + lane * VEC, v);
+        float s = 0.0f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            v[i] = (v[i] - mn[i]) / den[i];
+            s += v[i];
+        }
+        for (int o = lpr >> 1; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+        const float mean = s / float(D.d);
+        float q = 0.0f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            const float dv = v[i] - mean;
+            q += dv * dv;
+        }
+        for (int o = lpr >> 1; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+        if (lane == 0) sigma[unit * D.L + r] = sqrtf(q / float(D.d - D.ddof));
+    }
+}
+
+__device__ __forceinline__ float block_reduce(float v, bool is_max, float* sm) {
+    v = is_max ? wave_max(v) : wave_sum(v);
+    const int w = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm[w] = v;
+    __syncthreads();
+    float r = sm[0];
+    for (int i = 1; i < SCORE_THREADS / 64; ++i) r = is_max ? fmaxf(r, sm[i]) : r + sm[i];
+    return r;
+}
+
+__global__ __launch_bounds__(SCORE_THREADS) void k_softmax(Dims D, const float* __restrict__ sigma,
+                                                            float* __restrict__ score) {
+    const int p = blockIdx.x, bh = blockIdx.y;
+    const float* sk = sigma + ((int64_t(bh) * 2 + 0) * D.Ns + p) * D.L;
+    const float* sv = sigma + ((int64_t(bh) * 2 + 1) * D.Ns + p) * D.L;
+    __shared__ float sm[SCORE_THREADS / 64];
+    float mk = -INFINITY, mv = -INFINITY;
+    for (int r = threadIdx.x; r < D.L; r += SCORE_THREADS) {
+        mk = fmaxf(mk, sk[r]);
+        mv = fmaxf(mv, sv[r]);
+    }
+    mk = block_reduce(mk, true, sm);
+    mv = block_reduce(mv, true, sm);
+    float zk = 0.0f, zv = 0.0f;
+    for (int r = threadIdx.x; r < D.L; r += SCORE_THREADS) {
+        zk += expf(sk[r] - mk);
+        zv += expf(sv[r] - mv);
+    }
+    zk = block_reduce(zk, false, sm);
+    zv = block_reduce(zv, false, sm);
+    float* out = score + (int64_t(bh) * D.Ns + p) * D.L;
+    for (int r = threadIdx.x; r < D.L; r += SCORE_THREADS)
+        out[r] = expf(sk[r] - mk) / zk + expf(sv[r] - mv) / zv;
+}
+
+template <typename T>
+static hipError_t run_score(const Dims& D, const void* K, const void* V, float* score, void* ws, hipStream_t st) {
+    float* mm = reinterpret_cast<float*>(ws);
+    float* sigma = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + align256(mm_floats(D) * 4));
+    const dim3 grid(score_splits(D.L), D.Ns, D.B * D.Hkv * 2);
+    hipLaunchKernelGGL(k_minmax<T>, grid, dim3(SCORE_THREADS), 0, st, D, (const T*)K, (const T*)V, mm);
+    hipLaunchKernelGGL(k_sigma<T>, grid, dim3(SCORE_THREADS), 0, st, D, (const T*)K, (const T*)V, mm, sigma);
+    hipLaunchKernelGGL(k_softmax, dim3(D.Ns, D.B * D.Hkv), dim3(SCORE_THREADS), 0, st, D, sigma, score);
+    return hipGetLastError();
+}
+
+hipError_t launch_score(const Dims& D, const void* K, const void* V, float* score, void* ws, hipStream_t st) {
+    if (D.Ns == 0) return hipSuccess;
+    return D.dtype == 0 ? run_score<float>(D, K, V, score, ws, st) : run_score<bf16_t>(D, K, V, score, ws, st);
+}
+
+}  // namespace lrsa

@@ -1,0 +1,243 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the same seeded inputs.
+
+Bars (written out here as the tests' tolerances):
+  * selection, given the oracle's fp32 scores: bit-exact (integer work);
+  * scores: 2e-5 relative to the oracle's fp32 scores (both sides are fp32, the summation
+    orders differ);
+  * end-to-end selection (HIP scores -> HIP select): every index on which the two sides differ
+    must have an oracle fp32 score within 1e-6 of the oracle's K-th largest score of that chunk;
+  * O, dQ, dK, dV: max|x-ref|/max|ref| and ||x-ref||/||ref|| below 1e-4 (fp32) or 2e-2 (bf16)
+    against the fp64 oracle fed the same stored inputs and the oracle's idx; lse within 1e-3.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2506_11498_amd as lrsa
+from paper_2506_11498_amd import inputs
+from oracle import lrsa_ref as ref
+from oracle import lrsa_rows as rows
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def tol(dtype):
+    return 1e-4 if dtype == "f32" else 2e-2
+
+
+def rel_errs(x, r):
+    x = np.asarray(x, np.float64); r = np.asarray(r, np.float64)
+    return np.abs(x - r).max() / max(np.abs(r).max(), 1e-30), np.linalg.norm(x - r) / max(np.linalg.norm(r), 1e-30)
+
+
+def assert_close(name, x, r, t):
+    e_max, e_l2 = rel_errs(x, r)
+    assert e_max < t and e_l2 < t, f"{name}: max-rel {e_max:.3e}, l2-rel {e_l2:.3e} (bar {t:g})"
+
+
+def to_np(t):
+    return t.detach().float().cpu().numpy()
+
+
+def params(w, x, **kw):
+    return lrsa.params_for(x["Q"], x["K"], sink=w.S, lag=w.L, topk=w.K, **kw)
+
+
+def check_selection_in_tie_window(w, got, idx_ref, sc_ref):
+    """Returns the fraction of (b,h,p) windows that match exactly; asserts the tie-window bar."""
+    got = got.reshape(-1, w.K); want = idx_ref.reshape(-1, w.K); sc = sc_ref.reshape(-1, w.L)
+    exact = 0
+    for a, b, s in zip(got, want, sc):
+        base = b[0] - (b[0] - w.S) % w.L
+        assert np.all(np.diff(a) > 0) and a[0] >= base and a[-1] < base + w.L, "idx contract broken"
+        if np.array_equal(a, b):
+            exact += 1
+            continue
+        tau = np.sort(s)[-w.K]
+        diff = np.setxor1d(a, b)
+        assert np.all(np.abs(s[diff - base] - tau) <= 1e-6), "selection differs outside the tie window"
+    return exact / max(len(got), 1)
+
+
+def run_score_select(w, xd, **kw):
+    p = params(w, xd, **kw)
+    score = lrsa.lrsa_score(p, xd["K"], xd["V"])
+    idx = lrsa.lrsa_select(p, score)
+    return p, score, idx
+
+
+# ------------------------------------------------------------------ small and edge shapes, dense oracle
+SMALL = [
+    dict(name="tail", n=3 + 5 * 16 + 7, L=16, S=3, K=4, d=64, Hq=2, Hkv=1, B=2, dtype="f32"),
+    dict(name="no_tail", n=4 + 6 * 16, L=16, S=4, K=5, d=64, Hq=4, Hkv=2, B=1, dtype="f32"),
+    dict(name="no_sink", n=0 + 5 * 24 + 1, L=24, S=0, K=6, d=128, Hq=2, Hkv=2, B=1, dtype="f32"),
+    dict(name="keep_all", n=5 + 4 * 16 + 3, L=16, S=5, K=16, d=64, Hq=2, Hkv=1, B=1, dtype="f32"),
+    dict(name="keep_one", n=2 + 4 * 10 + 9, L=10, S=2, K=1, d=64, Hq=3, Hkv=1, B=1, dtype="f32"),
+    dict(name="nothing_compressed", n=6 + 2 * 32, L=32, S=6, K=8, d=64, Hq=2, Hkv=1, B=1, dtype="f32"),
+    dict(name="shorter_than_sink", n=5, L=8, S=16, K=2, d=64, Hq=1, Hkv=1, B=1, dtype="f32"),
+    dict(name="one_token", n=1, L=8, S=0, K=2, d=64, Hq=1, Hkv=1, B=1, dtype="f32"),
+    dict(name="bf16_d64", n=8 + 5 * 32 + 11, L=32, S=8, K=8, d=64, Hq=4, Hkv=2, B=1, dtype="bf16"),
+    dict(name="bf16_d128_gqa", n=16 + 6 * 64 + 40, L=64, S=16, K=16, d=128, Hq=8, Hkv=2, B=2, dtype="bf16"),
+    dict(name="bf16_odd_sizes", n=5 + 7 * 100 + 33, L=100, S=5, K=37, d=128, Hq=2, Hkv=1, B=1, dtype="bf16"),
+    dict(name="bf16_long_tiles", n=64 + 4 * 512 + 300, L=512, S=64, K=128, d=128, Hq=2, Hkv=1, B=1, dtype="bf16"),
+]
+
+
+@pytest.mark.parametrize("impl", [lrsa.IMPL_AUTO, lrsa.IMPL_GENERIC], ids=["auto", "generic"])
+@pytest.mark.parametrize("cfg", SMALL, ids=[c["name"] for c in SMALL])
+@pytest.mark.parametrize("local_prev", [1, 2])
+def test_small_shapes_against_dense_oracle(cfg, impl, local_prev):
+    if local_prev == 2 and cfg["name"] not in ("tail", "bf16_d128_gqa", "bf16_odd_sizes"):
+        pytest.skip("local_prev=2 is exercised on three shapes")
+    cfg = {k: v for k, v in cfg.items() if k != "name"}
+    w = inputs.small_workload(**cfg)
+    x = inputs.make_inputs(w)
+    xf = {k: v.float().numpy() for k, v in x.items()}
+    xd = {k: v.to(DEV) for k, v in x.items()}
+    Ns = ref.partition(w.n, w.S, w.L, local_prev)["Ns"]
+    p, score, idx = run_score_select(w, xd, local_prev=local_prev, impl=impl)
+    assert lrsa.num_scored_chunks(p) == Ns
+    if Ns:
+        sc_ref = ref.score(xf["K"], xf["V"], w.S, w.L, local_prev=local_prev)
+        idx_ref = ref.select(sc_ref, w.S, w.L, w.K)
+        assert np.allclose(to_np(score), sc_ref, rtol=2e-5, atol=1e-9)
+        sel_from_ref = lrsa.lrsa_select(p, torch.from_numpy(sc_ref).to(DEV))
+        assert np.array_equal(sel_from_ref.cpu().numpy(), idx_ref)
+        check_selection_in_tie_window(w, idx.cpu().numpy(), idx_ref, sc_ref)
+        idx_dev = torch.from_numpy(idx_ref).to(DEV)
+    else:
+        idx_ref, idx_dev = None, None
+    O, lse = lrsa.lrsa_attn_fwd(p, xd["Q"], xd["K"], xd["V"], idx_dev)
+    dQ, dK, dV = lrsa.lrsa_attn_bwd(p, xd["Q"], xd["K"], xd["V"], O, xd["dO"], lse, idx_dev)
+    O_ref, lse_ref = ref.attn_fwd_dense(xf["Q"], xf["K"], xf["V"], idx_ref, w.S, w.L, local_prev=local_prev)
+    g = ref.attn_bwd_dense(xf["Q"], xf["K"], xf["V"], xf["dO"], idx_ref, w.S, w.L, local_prev=local_prev)
+    t = tol(w.dtype)
+    assert_close("O", to_np(O), O_ref, t)
+    assert np.abs(to_np(lse) - lse_ref).max() < 1e-3
+    # the backward was fed the HIP path's own (rounded) O; the oracle's D uses its exact O
+    assert_close("dQ", to_np(dQ), g[0], t)
+    assert_close("dK", to_np(dK), g[1], t)
+    assert_close("dV", to_np(dV), g[2], t)
+
+
+def test_uniform_chunk_ties_go_to_lowest_positions():
+    w = inputs.small_workload(n=4 + 5 * 64, L=64, S=4, K=16, d=64, Hq=1, Hkv=1)
+    x = inputs.make_inputs(w)
+    for k in ("K", "V"):
+        x[k][0, 0, w.S + w.L: w.S + 2 * w.L] = x[k][0, 0, w.S + w.L]       # chunk 1 uniform
+    xd = {k: v.to(DEV) for k, v in x.items()}
+    _, score, idx = run_score_select(w, xd)
+    sc = to_np(score)[0, 0, 1]
+    assert np.all(sc == sc[0]) and abs(sc[0] - 2.0 / w.L) < 1e-7
+    assert list(idx.cpu().numpy()[0, 0, 1]) == list(range(w.S + w.L, w.S + w.L + w.K))
+
+
+def test_select_is_exact_on_heavily_tied_scores():
+    rng = np.random.default_rng(5)
+    w = inputs.small_workload(n=3 + 9 * 300 + 5, L=300, S=3, K=77, d=64, Hq=1, Hkv=2, B=2)
+    Ns = ref.partition(w.n, w.S, w.L)["Ns"]
+    sc = rng.choice(np.array([1e-3, 2e-3, 2.0000002e-3, 3e-3], np.float32), size=(w.B, w.Hkv, Ns, w.L))
+    x = {k: v.to(DEV) for k, v in inputs.make_inputs(w).items()}
+    p = params(w, x)
+    got = lrsa.lrsa_select(p, torch.from_numpy(sc).to(DEV)).cpu().numpy()
+    assert np.array_equal(got, ref.select(sc, w.S, w.L, w.K))
+
+
+def test_strided_views_and_preallocated_outputs():
+    """Q/K/V given as [B, n, H, d] storage viewed as [B, H, n, d] (position stride = H*d)."""
+    w = inputs.small_workload(n=8 + 5 * 32 + 3, L=32, S=8, K=8, d=128, Hq=4, Hkv=2, B=2, dtype="bf16")
+    x = inputs.make_inputs(w)
+    xf = {k: v.float().numpy() for k, v in x.items()}
+    xd = {k: v.permute(0, 2, 1, 3).contiguous().to(DEV).permute(0, 2, 1, 3) for k, v in x.items()}
+    assert xd["Q"].stride(2) == w.Hq * w.d
+    p, score, idx = run_score_select(w, xd)
+    sc_ref = ref.score(xf["K"], xf["V"], w.S, w.L)
+    idx_ref = ref.select(sc_ref, w.S, w.L, w.K)
+    assert np.allclose(to_np(score), sc_ref, rtol=2e-5, atol=1e-9)
+    idx_dev = torch.from_numpy(idx_ref).to(DEV)
+    O, lse = lrsa.lrsa_attn_fwd(p, xd["Q"], xd["K"], xd["V"], idx_dev)
+    assert O.stride() == xd["Q"].stride()
+    dQ, dK, dV = lrsa.lrsa_attn_bwd(p, xd["Q"], xd["K"], xd["V"], O, xd["dO"], lse, idx_dev)
+    O_ref, _ = ref.attn_fwd_dense(xf["Q"], xf["K"], xf["V"], idx_ref, w.S, w.L)
+    g = ref.attn_bwd_dense(xf["Q"], xf["K"], xf["V"], xf["dO"], idx_ref, w.S, w.L)
+    for name, a, b in (("O", O, O_ref), ("dQ", dQ, g[0]), ("dK", dK, g[1]), ("dV", dV, g[2])):
+        assert_close(name, to_np(a), b, 2e-2)
+
+
+def test_runs_are_deterministic():
+    w = inputs.small_workload(n=16 + 6 * 128 + 50, L=128, S=16, K=32, d=128, Hq=4, Hkv=2, B=1, dtype="bf16")
+    xd = {k: v.to(DEV) for k, v in inputs.make_inputs(w).items()}
+    outs = []
+    for _ in range(2):
+        p, score, idx = run_score_select(w, xd)
+        O, lse = lrsa.lrsa_attn_fwd(p, xd["Q"], xd["K"], xd["V"], idx)
+        g = lrsa.lrsa_attn_bwd(p, xd["Q"], xd["K"], xd["V"], O, xd["dO"], lse, idx)
+        outs.append([t.clone() for t in (score, idx, O, lse, *g)])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+# ------------------------------------------------------------------ the five workloads
+def full_workload_parity(name, kv_heads, batch=0, n_rows=None, n_cols=None, late_cols_only=False, seed=0):
+    """Score / select on every head; attention on the listed KV groups of one batch entry,
+    either in full or on sampled rows / columns."""
+    w = inputs.WORKLOADS[name]
+    x = inputs.make_inputs(w)
+    xd = {k: v.to(DEV) for k, v in x.items()}
+    Kf, Vf = x["K"].float().numpy(), x["V"].float().numpy()
+    sc_ref = ref.score(Kf, Vf, w.S, w.L)
+    idx_ref = ref.select(sc_ref, w.S, w.L, w.K)
+    p, score, idx = run_score_select(w, xd)
+    assert np.allclose(to_np(score), sc_ref, rtol=2e-5, atol=1e-9)
+    assert np.array_equal(lrsa.lrsa_select(p, torch.from_numpy(sc_ref).to(DEV)).cpu().numpy(), idx_ref)
+    exact = check_selection_in_tie_window(w, idx.cpu().numpy(), idx_ref, sc_ref)
+    print(f"{name}: end-to-end selection exact on {100 * exact:.2f}% of windows")
+    idx_dev = torch.from_numpy(idx_ref).to(DEV)
+    O, lse = lrsa.lrsa_attn_fwd(p, xd["Q"], xd["K"], xd["V"], idx_dev)
+    dQ, dK, dV = lrsa.lrsa_attn_bwd(p, xd["Q"], xd["K"], xd["V"], O, xd["dO"], lse, idx_dev)
+    torch.cuda.synchronize()
+    t = tol(w.dtype)
+    rng = np.random.default_rng(seed)
+    G = w.G
+    for h in kv_heads:
+        sl = slice(h * G, (h + 1) * G)
+        Qg, dOg = x["Q"][batch, sl].float().numpy(), x["dO"][batch, sl].float().numpy()
+        args = (Qg, Kf[batch, h], Vf[batch, h], dOg, idx_ref[batch, h])
+        if n_rows is None:
+            r = rows.attn_group(*args, w.S, w.L, w.K)
+            rsel = csel = np.arange(w.n)
+        else:
+            # rows: every segment boundary plus random ones; columns: sink, survivors, dropped
+            edges = [0, w.S - 1, w.S, w.S + w.L - 1, w.S + w.L, w.S + 2 * w.L, w.n - 1, w.n - 2]
+            rsel = np.unique(np.clip(np.concatenate([edges, rng.integers(0, w.n, n_rows)]), 0, w.n - 1))
+            lo = w.n - 3 * w.L if late_cols_only else 0
+            csel = np.unique(np.concatenate([rng.integers(lo, w.n, n_cols), idx_ref[batch, h, -1, :4],
+                                             [] if late_cols_only else [0, w.S - 1, w.S, idx_ref[batch, h, 0, 0]]])).astype(np.int64)
+            r = rows.attn_rows(*args, rsel, w.S, w.L, w.K)
+            r.update(rows.attn_cols(*args, csel, w.S, w.L, w.K))
+        assert_close(f"O[h{h}]", to_np(O[batch, sl][:, rsel]), r["O"], t)
+        assert np.abs(to_np(lse[batch, sl][:, rsel]) - r["lse"]).max() < 1e-3
+        assert_close(f"dQ[h{h}]", to_np(dQ[batch, sl][:, rsel]), r["dQ"], t)
+        assert_close(f"dK[h{h}]", to_np(dK[batch, h][csel]), r["dK"], t)
+        assert_close(f"dV[h{h}]", to_np(dV[batch, h][csel]), r["dV"], t)
+
+
+def test_workload_C1_tiny_fp32():
+    full_workload_parity("C1", kv_heads=[0])
+
+
+def test_workload_C2_small_bf16():
+    full_workload_parity("C2", kv_heads=[0, 5], batch=1)
+
+
+def test_workload_C3_llama7b_shaped():
+    full_workload_parity("C3", kv_heads=[7], n_rows=192, n_cols=48)
+
+
+def test_workload_C4_gqa_32k():
+    full_workload_parity("C4", kv_heads=[3], n_rows=192, n_cols=32)
+
+
+def test_workload_C5_stress_128k():
+    full_workload_parity("C5", kv_heads=[6], n_rows=96, n_cols=12, late_cols_only=True)
