@@ -127,6 +127,15 @@ int lrsa_attn_bwd(const lrsa_params *p, const void *Q, const void *K, const void
 /* Message of the calling thread's last failed call (static thread-local storage, never NULL). */
 const char *lrsa_last_error(void);
 
+/* Per-kernel timing for benchmarks (not part of the paper's method).  lrsa_timing_enable(1) clears
+ * the records and makes every later call bracket each of its kernel launches with HIP events on
+ * the call's stream; lrsa_timing_enable(0) clears and stops.  lrsa_timing_count() is the number of
+ * launches recorded so far (at most 4096); lrsa_timing_read(i, &name, &ms) waits for launch i and
+ * returns its kernel's name (static storage) and duration in milliseconds. */
+int lrsa_timing_enable(int on);
+int lrsa_timing_count(void);
+int lrsa_timing_read(int i, const char **name, float *ms);
+
 /* ABI revision of this header; bumped when a signature or the struct changes. */
 int lrsa_abi_version(void);
 

@@ -20,7 +20,8 @@ IMPL_AUTO, IMPL_GENERIC = 0, 1
 WS_SCORE, WS_SELECT, WS_ATTN_FWD, WS_ATTN_BWD = 0, 1, 2, 3
 
 EXPORTS = ("lrsa_abi_version", "lrsa_last_error", "lrsa_num_scored_chunks", "lrsa_workspace_bytes",
-           "lrsa_score", "lrsa_select", "lrsa_attn_fwd", "lrsa_attn_bwd")
+           "lrsa_score", "lrsa_select", "lrsa_attn_fwd", "lrsa_attn_bwd",
+           "lrsa_timing_enable", "lrsa_timing_count", "lrsa_timing_read")
 
 
 class LrsaParams(ctypes.Structure):
@@ -164,3 +165,19 @@ def lrsa_attn_bwd(p: LrsaParams, Q, K, V, O, dO, lse, idx, dQ=None, dK=None, dV=
     _check(lib().lrsa_attn_bwd(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(lse), _ptr(idx),
                                _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ws), nb, _stream()))
     return dQ, dK, dV
+
+
+def timing_enable(on: bool) -> None:
+    """Switch per-kernel HIP-event timing on (clearing earlier records) or off."""
+    _check(lib().lrsa_timing_enable(1 if on else 0))
+
+
+def timing_records():
+    """[(kernel name, milliseconds)] of every launch recorded since timing was switched on (waits for them)."""
+    L = lib()
+    out = []
+    name, ms = ctypes.c_char_p(), ctypes.c_float()
+    for i in range(L.lrsa_timing_count()):
+        _check(L.lrsa_timing_read(i, ctypes.byref(name), ctypes.byref(ms)))
+        out.append((name.value.decode(), ms.value))
+    return out

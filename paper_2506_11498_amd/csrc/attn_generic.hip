@@ -262,7 +262,7 @@ size_t attn_bwd_generic_ws_bytes(const Dims& D) { return align256(size_t(D.B) * 
 template <typename T, int DH>
 static hipError_t run_fwd(const Dims& D, const void* Q, const void* K, const void* V, const int32_t* idx, void* O,
                           float* lse, hipStream_t st) {
-    hipLaunchKernelGGL((k_fwd_generic<T, DH>), dim3(D.n, D.Hq, D.B), dim3(64), 0, st, D, (const T*)Q, (const T*)K,
+    LRSA_TIMED_LAUNCH("k_fwd_genericT", st, (k_fwd_generic<T, DH>), dim3(D.n, D.Hq, D.B), dim3(64), 0, st, D, (const T*)Q, (const T*)K,
                        (const T*)V, idx, (T*)O, lse);
     return hipGetLastError();
 }
@@ -272,9 +272,9 @@ static hipError_t run_bwd(const Dims& D, const void* Q, const void* K, const voi
                           const float* lse, const int32_t* idx, void* dQ, void* dK, void* dV, void* ws,
                           hipStream_t st) {
     float* Dsum = reinterpret_cast<float*>(ws);
-    hipLaunchKernelGGL((k_bwd_dq_generic<T, DH>), dim3(D.n, D.Hq, D.B), dim3(64), 0, st, D, (const T*)Q, (const T*)K,
+    LRSA_TIMED_LAUNCH("k_bwd_dq_genericT", st, (k_bwd_dq_generic<T, DH>), dim3(D.n, D.Hq, D.B), dim3(64), 0, st, D, (const T*)Q, (const T*)K,
                        (const T*)V, (const T*)O, (const T*)dO, lse, idx, (T*)dQ, Dsum);
-    hipLaunchKernelGGL((k_bwd_dkv_generic<T, DH>), dim3(D.n, D.Hkv, D.B), dim3(64), 0, st, D, (const T*)Q,
+    LRSA_TIMED_LAUNCH("k_bwd_dkv_genericT", st, (k_bwd_dkv_generic<T, DH>), dim3(D.n, D.Hkv, D.B), dim3(64), 0, st, D, (const T*)Q,
                        (const T*)K, (const T*)V, (const T*)dO, lse, Dsum, idx, (T*)dK, (T*)dV);
     return hipGetLastError();
 }

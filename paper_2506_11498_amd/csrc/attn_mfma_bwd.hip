@@ -455,18 +455,18 @@ hipError_t launch_attn_bwd_mfma(const Dims& D, const void* Q, const void* K, con
                  *g = (const bf16_t*)dO;
 
     const int64_t nrows = int64_t(D.B) * D.Hq * D.n;
-    hipLaunchKernelGGL(k_bwd_rowdot, dim3((unsigned)((nrows + 15) / 16)), dim3(BWD_THREADS), 0, st, D, o, g, Dsum);
+    LRSA_TIMED_LAUNCH("k_bwd_rowdot", st, k_bwd_rowdot, dim3((unsigned)((nrows + 15) / 16)), dim3(BWD_THREADS), 0, st, D, o, g, Dsum);
 
     const int qtiles = P.sink_tiles_q + D.nq * P.tpc_q;
     if (qtiles > 0)
-        hipLaunchKernelGGL(k_bwd_dq, dim3(qtiles, D.Hq, D.B), dim3(BWD_THREADS), 0, st, D, q, k, v, g, lse, Dsum, idx,
+        LRSA_TIMED_LAUNCH("k_bwd_dq", st, k_bwd_dq, dim3(qtiles, D.Hq, D.B), dim3(BWD_THREADS), 0, st, D, q, k, v, g, lse, Dsum, idx,
                            (bf16_t*)dQ, P.sink_tiles_q, P.tpc_q);
     if (P.gtiles > 0)
-        hipLaunchKernelGGL(k_bwd_dkv<true>, dim3(P.gtiles * P.nsl, D.Hkv, D.B), dim3(BWD_THREADS), 0, st, D, q, k, v,
+        LRSA_TIMED_LAUNCH("k_bwd_dkvtrue", st, k_bwd_dkv<true>, dim3(P.gtiles * P.nsl, D.Hkv, D.B), dim3(BWD_THREADS), 0, st, D, q, k, v,
                            g, lse, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
     const int ktiles = P.sink_tiles_k + D.nq * P.tpc_k;
     if (ktiles > 0)
-        hipLaunchKernelGGL(k_bwd_dkv<false>, dim3(ktiles, D.Hkv, D.B), dim3(BWD_THREADS), 0, st, D, q, k, v, g, lse,
+        LRSA_TIMED_LAUNCH("k_bwd_dkvfalse", st, k_bwd_dkv<false>, dim3(ktiles, D.Hkv, D.B), dim3(BWD_THREADS), 0, st, D, q, k, v, g, lse,
                            Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
     return hipGetLastError();
 }

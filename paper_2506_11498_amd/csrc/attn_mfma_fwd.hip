@@ -192,7 +192,7 @@ hipError_t launch_attn_fwd_mfma(const Dims& D, const void* Q, const void* K, con
     const int tpc = (D.L + FWD_BM - 1) / FWD_BM;
     const int tiles = sink_tiles + D.nq * tpc;
     if (tiles == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_fwd_mfma, dim3(tiles, D.Hq, D.B), dim3(FWD_THREADS), 0, st, D, (const bf16_t*)Q,
+    LRSA_TIMED_LAUNCH("k_fwd_mfma", st, k_fwd_mfma, dim3(tiles, D.Hq, D.B), dim3(FWD_THREADS), 0, st, D, (const bf16_t*)Q,
                        (const bf16_t*)K, (const bf16_t*)V, idx, (bf16_t*)O, lse, sink_tiles, tpc);
     return hipGetLastError();
 }

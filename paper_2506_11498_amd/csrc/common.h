@@ -55,6 +55,22 @@ hipError_t launch_attn_bwd_mfma(const Dims&, const void* Q, const void* K, const
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
+// Brackets one kernel launch with HIP events on its stream when timing is switched on
+// (lrsa_timing_enable); does nothing otherwise.
+class ScopedKernelTimer {
+  public:
+    ScopedKernelTimer(const char* name, hipStream_t st);
+    ~ScopedKernelTimer();
+  private:
+    hipStream_t st_;
+    int slot_;
+};
+#define LRSA_TIMED_LAUNCH(name, st, ...)            \
+    do {                                            \
+        ::lrsa::ScopedKernelTimer timer_(name, st); \
+        hipLaunchKernelGGL(__VA_ARGS__);            \
+    } while (0)
+
 // ---- device helpers ---------------------------------------------------------------------------
 #if defined(__HIPCC__)
 typedef uint16_t bf16_t;  // raw bfloat16 bits

@@ -175,9 +175,9 @@ static hipError_t run_score(const Dims& D, const void* K, const void* V, float* 
     float* mm = reinterpret_cast<float*>(ws);
     float* sigma = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + align256(mm_floats(D) * 4));
     const dim3 grid(score_splits(D.L), D.Ns, D.B * D.Hkv * 2);
-    hipLaunchKernelGGL(k_minmax<T>, grid, dim3(SCORE_THREADS), 0, st, D, (const T*)K, (const T*)V, mm);
-    hipLaunchKernelGGL(k_sigma<T>, grid, dim3(SCORE_THREADS), 0, st, D, (const T*)K, (const T*)V, mm, sigma);
-    hipLaunchKernelGGL(k_softmax, dim3(D.Ns, D.B * D.Hkv), dim3(SCORE_THREADS), 0, st, D, sigma, score);
+    LRSA_TIMED_LAUNCH("k_minmaxT", st, k_minmax<T>, grid, dim3(SCORE_THREADS), 0, st, D, (const T*)K, (const T*)V, mm);
+    LRSA_TIMED_LAUNCH("k_sigmaT", st, k_sigma<T>, grid, dim3(SCORE_THREADS), 0, st, D, (const T*)K, (const T*)V, mm, sigma);
+    LRSA_TIMED_LAUNCH("k_softmax", st, k_softmax, dim3(D.Ns, D.B * D.Hkv), dim3(SCORE_THREADS), 0, st, D, sigma, score);
     return hipGetLastError();
 }
 

@@ -93,7 +93,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(Dims D, const float* __r
 
 hipError_t launch_select(const Dims& D, const float* score, int32_t* idx, void*, hipStream_t st) {
     if (D.Ns == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_select, dim3(D.Ns, D.B * D.Hkv), dim3(SEL_THREADS), 0, st, D, score, idx);
+    LRSA_TIMED_LAUNCH("k_select", st, k_select, dim3(D.Ns, D.B * D.Hkv), dim3(SEL_THREADS), 0, st, D, score, idx);
     return hipGetLastError();
 }
 
