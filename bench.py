@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the LRSA hot path on one MI355X.
+
+A step is one pass of the whole path -- lrsa_score, lrsa_select, lrsa_attn_fwd, lrsa_attn_bwd --
+over one synthetic batch that is already resident in HBM.  The workload is the 32K-token GQA
+config ("C4": B1, 32 query / 8 KV heads, d 128, n 32768, L 1024, K 256, S 64, bf16) unless
+--workload says otherwise.  Prints ONE JSON line:
+
+  value      effective TFLOP/s of attention forward+backward = 14*d*pairs*Hq*B / time of a
+             whole step (score and select included in the time), pairs = visible (query, key)
+             pairs per query head
+  roofline   the kernel with the largest share of the step, its algorithmic flops per launch
+             over its HIP-event duration, against the dense bf16 MFMA peak
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload
+
+K and V are rotated over several copies so that the scoring kernels read HBM-cold data.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBPS = 8000.0
+
+
+def pair_counts(w, local_prev=1):
+    """(all visible pairs, pairs reached through the gather list) per query head, from the mask's
+    closed form: a row of chunk q sees S + K*max(q-lp,0) gathered keys plus the window back to the
+    start of chunk max(q-lp,0)."""
+    import numpy as np
+    t = np.arange(w.n, dtype=np.int64)
+    q = (t - w.S) // w.L
+    c = np.maximum(q - local_prev, 0)
+    gathered = np.where(t < w.S, 0, w.S + w.K * c)
+    window = np.where(t < w.S, t + 1, t - (w.S + w.L * c) + 1)
+    return int((gathered + window).sum()), int(gathered.sum())
+
+
+def cpu_baseline(w, x, idx_ref_holder):
+    """Time the oracle on a bounded sample: scores and selection of every head (NumPy fp32),
+    then forward + dQ of every 16th row of one KV group (C code, fp64, OpenMP)."""
+    import numpy as np
+    from oracle import lrsa_ref as ref
+    from oracle import lrsa_rows as rows
+    Kf, Vf = x["K"].float().numpy(), x["V"].float().numpy()
+    t0 = time.perf_counter()
+    sc = ref.score(Kf, Vf, w.S, w.L)
+    idx = ref.select(sc, w.S, w.L, w.K)
+    t_sel = time.perf_counter() - t0
+    idx_ref_holder.append(idx)
+    G = w.G
+    pick = np.arange(0, w.n, 16)
+    Qg, dOg = x["Q"][0, :G].float().numpy(), x["dO"][0, :G].float().numpy()
+    t0 = time.perf_counter()
+    rows.attn_rows(Qg, Kf[0, 0], Vf[0, 0], dOg, idx[0, 0], pick, w.S, w.L, w.K)
+    t_rows = time.perf_counter() - t0
+    t = pick
+    q = (t - w.S) // w.L
+    c = np.maximum(q - 1, 0)
+    pairs = int(np.where(t < w.S, t + 1, w.S + w.K * c + t - (w.S + w.L * c) + 1).sum())
+    flops = 8.0 * w.d * pairs * G            # logits, O, dA, dQ: 2*d flop each per pair and head
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": flops / t_rows / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"fp64 forward+dQ of every 16th row of KV group 0 ({len(pick)} rows x {G} heads, "
+                      f"{t_rows:.1f} s); fp32 score+select of all heads took {t_sel:.2f} s",
+            "score_select_s": t_sel}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C4")
+    ap.add_argument("--kv-copies", type=int, default=4, help="distinct K/V copies rotated over the steps")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2506_11498_amd as lrsa
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    w = lrsa.inputs.WORKLOADS[args.workload]
+    x = lrsa.inputs.make_inputs(w)
+    Q, dO = x["Q"].to(dev), x["dO"].to(dev)
+    Ks = [x["K"].to(dev) for _ in range(max(args.kv_copies, 1))]
+    Vs = [x["V"].to(dev) for _ in range(max(args.kv_copies, 1))]
+    p = lrsa.params_for(Q, Ks[0], sink=w.S, lag=w.L, topk=w.K)
+    Ns = lrsa.num_scored_chunks(p)
+    score = torch.empty((w.B, w.Hkv, Ns, w.L), dtype=torch.float32, device=dev)
+    idx = torch.empty((w.B, w.Hkv, Ns, w.K), dtype=torch.int32, device=dev)
+    O, dQ = torch.empty_like(Q), torch.empty_like(Q)
+    lse = torch.empty((w.B, w.Hq, w.n), dtype=torch.float32, device=dev)
+    dK, dV = torch.empty_like(Ks[0]), torch.empty_like(Ks[0])
+    ws_bytes = max(lrsa.workspace_bytes(p, k) for k in range(4))
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+
+    def step(i):
+        K, V = Ks[i % len(Ks)], Vs[i % len(Vs)]
+        lrsa.lrsa_score(p, K, V, score, ws)
+        lrsa.lrsa_select(p, score, idx, ws)
+        lrsa.lrsa_attn_fwd(p, Q, K, V, idx, O, lse, ws)
+        lrsa.lrsa_attn_bwd(p, Q, K, V, O, dO, lse, idx, dQ, dK, dV, ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    lrsa.timing_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    recs = lrsa.timing_records()
+    lrsa.timing_enable(False)
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    per_kernel = {}
+    for name, ms in recs:
+        per_kernel.setdefault(name, []).append(ms)
+    kern_ms = {k: sum(v) / len(v) for k, v in per_kernel.items()}           # average launch duration
+    launches = {k: len(v) / args.steps for k, v in per_kernel.items()}
+
+    pairs, pairs_g = pair_counts(w)
+    unit = w.d * w.Hq * w.B
+    flops_step = 14.0 * unit * pairs
+    # algorithmic flops per launch: forward 4*d per pair; backward 10*d per pair = S, dA, dV, dK
+    # (8*d, in the key-outer kernels) + dQ (2*d, in the query-outer kernel)
+    kern_flops = {"k_fwd_mfma": 4.0 * unit * pairs, "k_bwd_dq": 2.0 * unit * pairs,
+                  "k_bwd_dkvtrue": 8.0 * unit * pairs_g, "k_bwd_dkvfalse": 8.0 * unit * (pairs - pairs_g)}
+    cand = [k for k in kern_flops if k in kern_ms]
+    roofline = None
+    if cand:
+        dom = max(cand, key=lambda k: kern_ms[k] * launches[k])
+        ach = kern_flops[dom] / (kern_ms[dom] * 1e-3) / 1e12
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "traffic.json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get(f"{dom}:{w.name}")
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic, "avg_launch_ms": kern_ms[dom],
+                    "algorithmic_flop_per_launch": kern_flops[dom]}
+
+    def stage(names):
+        return sum(kern_ms.get(k, 0.0) * launches.get(k, 0.0) for k in names)
+    esz = 2 if w.dtype == "bf16" else 4
+    score_bytes = 2 * w.B * w.Hkv * w.n * w.d * esz + 4 * w.B * w.Hkv * Ns * w.L
+    ms_score = stage(["k_minmaxT", "k_sigmaT", "k_softmax"])
+    ms_select = stage(["k_select"])
+    ms_fwd = stage(["k_fwd_mfma", "k_fwd_genericT"])
+    ms_bwd = stage(["k_bwd_rowdot", "k_bwd_dq", "k_bwd_dkvtrue", "k_bwd_dkvfalse", "k_bwd_dq_genericT", "k_bwd_dkv_genericT"])
+    ss_bytes = score_bytes + 4 * w.B * w.Hkv * Ns * w.K     # K and V read once, scores and idx written once
+    ss_gbps = ss_bytes / max(ms_score + ms_select, 1e-9) / 1e6
+    out = {
+        "metric": "lrsa_attn_fwd_bwd_effective_tflops_32k_bf16" if w.name == "C4" else f"lrsa_attn_fwd_bwd_effective_tflops_{w.name}",
+        "value": flops_step / elapsed * args.steps / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: B{w.B} Hq{w.Hq} Hkv{w.Hkv} d{w.d} n{w.n} L{w.L} K{w.K} S{w.S} {w.dtype}, {w.structure}",
+                   "pairs_per_head": pairs, "kv_copies": len(Ks)},
+        "tokens_per_s": w.B * w.n / (ms_per_step * 1e-3),
+        "attn_fwd_bwd_tflops_kernels_only": flops_step / max((ms_fwd + ms_bwd) * 1e-3, 1e-12) / 1e12,
+        "stages_ms": {"score": ms_score, "select": ms_select, "attn_fwd": ms_fwd, "attn_bwd": ms_bwd},
+        "score_select": {"GBps": ss_gbps, "frac_of_hbm_peak": ss_gbps / HBM_PEAK_GBPS,
+                         "algorithmic_bytes": ss_bytes},
+        "kernels_ms": kern_ms,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        holder = []
+        out["cpu_baseline"] = cpu_baseline(w, x, holder)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
