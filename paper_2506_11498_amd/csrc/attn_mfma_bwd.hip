@@ -85,6 +85,60 @@ __global__ __launch_bounds__(BWD_THREADS) void k_bwd_rowdot(Dims D, const bf16_t
 }
 
 // ------------------------------------------------------------------------------------ dQ
+// One 64-key tile for one wave: per 32 keys S^T and dA^T, then dS^T, then dQ^T += K^T dS^T.
+// MASK: the tile holds entries some query of the wave does not see (only the last tiles of a walk).
+template <bool MASK>
+__device__ __forceinline__ void dq_tile(const unsigned char* sK, const unsigned char* sV, const bf16x8 (&qf)[8],
+                                        const bf16x8 (&gf)[8], const LaneOffs& lo, f32x16 (&dq)[4], int j0, int lim,
+                                        int wave_lim_max, float c2, float lse2, float Dq, int lane) {
+    const int g = lane >> 5;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        if (!MASK || j0 + kb * 32 <= wave_lim_max) {  // otherwise these 32 keys are masked for the whole wave
+            f32x16 s, dp;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { s[i] = 0.0f; dp[i] = 0.0f; }
+            bf16x8 a[8], c[8];
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) a[kk] = read_rows_o(sK, lo, kb * 32, kk);
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                s = mfma32(a[kk], qf[kk], s);
+                c[kk] = read_rows_o(sV, lo, kb * 32, kk);
+            }
+            bf16x8 ka[4], kc[4];
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                dp = mfma32(c[kk], gf[kk], dp);
+                if (kk < 4) ka[kk] = read_cols_o(sK, lo, kb * 32, kk);
+            }
+            const float neg_l = -lse2;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float pr = fast_exp2(__builtin_fmaf(s[i], c2, neg_l));
+                if (MASK) {
+                    const int j = j0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+                    pr = j <= lim ? pr : 0.0f;
+                }
+                s[i] = pr * (dp[i] - Dq);
+            }
+            {
+                const bf16x8 dsf = pack8(s, 0);
+#pragma unroll
+                for (int db = 0; db < 4; ++db) {
+                    dq[db] = mfma32(ka[db], dsf, dq[db]);
+                    kc[db] = read_cols_o(sK, lo, kb * 32 + 16, db);
+                }
+            }
+            {
+                const bf16x8 dsf = pack8(s, 8);
+#pragma unroll
+                for (int db = 0; db < 4; ++db) dq[db] = mfma32(kc[db], dsf, dq[db]);
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(BWD_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t* __restrict__ Q,
                                                             const bf16_t* __restrict__ K,
                                                             const bf16_t* __restrict__ V,
@@ -93,8 +147,10 @@ __global__ __launch_bounds__(BWD_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t*
                                                             const float* __restrict__ Dsum,
                                                             const int32_t* __restrict__ idx,
                                                             bf16_t* __restrict__ dQ, int sink_tiles, int tpc) {
-    __shared__ __attribute__((aligned(16))) unsigned char sK[DQ_BN * TILE_ROW_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char sV[DQ_BN * TILE_ROW_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sK0[DQ_BN * TILE_ROW_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sV0[DQ_BN * TILE_ROW_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sK1[DQ_BN * TILE_ROW_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sV1[DQ_BN * TILE_ROW_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
@@ -136,69 +192,63 @@ __global__ __launch_bounds__(BWD_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t*
     const int lim = ng + tq - cs;
     const int wave_lim_max = ng + min(t0 + wave * 32 + 31, t_last) - cs;
 
-    const int kg4 = tid >> 4, c16 = tid & 15;
-    int pos0, pos1, pos2, pos3;
-    uint4 kr0, kr1, kr2, kr3, vr0, vr1, vr2, vr3;
-#define LRSA_POS(tile, e) stream_pos(D, idx_h, min((tile) * DQ_BN + 4 * kg4 + (e), m_max - 1), ng, cs)
-#define LRSA_FETCH_POS(tile) { pos0 = LRSA_POS(tile, 0); pos1 = LRSA_POS(tile, 1); pos2 = LRSA_POS(tile, 2); pos3 = LRSA_POS(tile, 3); }
-#define LRSA_LD(base, p) (*reinterpret_cast<const uint4*>((base) + int64_t(p) * D.ks[2] + c16 * 8))
-#define LRSA_ISSUE() { kr0 = LRSA_LD(Kh, pos0); kr1 = LRSA_LD(Kh, pos1); kr2 = LRSA_LD(Kh, pos2); kr3 = LRSA_LD(Kh, pos3); \
-                       vr0 = LRSA_LD(Vh, pos0); vr1 = LRSA_LD(Vh, pos1); vr2 = LRSA_LD(Vh, pos2); vr3 = LRSA_LD(Vh, pos3); }
-#define LRSA_ST(tile_base, e, v) (*reinterpret_cast<uint4*>((tile_base) + tile_off(4 * kg4 + (e), c16)) = (v))
-#define LRSA_STASH() { LRSA_ST(sK, 0, kr0); LRSA_ST(sK, 1, kr1); LRSA_ST(sK, 2, kr2); LRSA_ST(sK, 3, kr3); \
-                       LRSA_ST(sV, 0, vr0); LRSA_ST(sV, 1, vr1); LRSA_ST(sV, 2, vr2); LRSA_ST(sV, 3, vr3); }
+    int pos[4];
+    auto fetch_pos = [&](int tile) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int j = tile * DQ_BN + async_row(16 * wave + 4 * i, lane);
+            pos[i] = stream_pos(D, idx_h, j < m_max ? j : m_max - 1, ng, cs);
+        }
+    };
+    auto issue = [&](unsigned char* sK, unsigned char* sV) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r4 = 16 * wave + 4 * i;
+            const int64_t off = int64_t(pos[i]) * D.ks[2] + async_chunk(async_row(r4, lane), lane) * 8;
+            async_rows4(Kh + off, sK, r4);
+            async_rows4(Vh + off, sV, r4);
+        }
+    };
 
     const float c2 = D.scale * 1.4426950408889634f;
+    const LaneOffs lo = make_lane_offs(lane);
+    const int wave_lim_min = ng + t0 + wave * 32 - cs;   // last stream entry the wave's first query sees
+#define LRSA_DQ_TILE(sK, sV, j0_)                                                                              \
+    {                                                                                                           \
+        const int j0 = (j0_);                                                                                   \
+        if (j0 + DQ_BN - 1 <= wave_lim_min)                                                                     \
+            dq_tile<false>(sK, sV, qf, gf, lo, dq, j0, lim, wave_lim_max, c2, lse2, Dq, lane);                  \
+        else if (j0 <= wave_lim_max)                                                                            \
+            dq_tile<true>(sK, sV, qf, gf, lo, dq, j0, lim, wave_lim_max, c2, lse2, Dq, lane);                   \
+    }
     f32x16 dq[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) dq[db][i] = 0.0f;
 
-    LRSA_FETCH_POS(0);
-    LRSA_ISSUE();
-    if (ntiles > 1) LRSA_FETCH_POS(1);
-    for (int tile = 0; tile < ntiles; ++tile) {
-        LRSA_STASH();
+    fetch_pos(0);
+    issue(sK0, sV0);
+    if (ntiles > 1) fetch_pos(1);
+    for (int tile = 0; tile < ntiles; tile += 2) {
+        wait_vmcnt<0>();
         __syncthreads();
         if (tile + 1 < ntiles) {
-            LRSA_ISSUE();
-            if (tile + 2 < ntiles) LRSA_FETCH_POS(tile + 2);
+            issue(sK1, sV1);
+            if (tile + 2 < ntiles) fetch_pos(tile + 2);
         }
-        const int j0 = tile * DQ_BN;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            if (j0 + kb * 32 <= wave_lim_max) {  // otherwise these 32 keys are masked for the whole wave
-                f32x16 s, dp;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) { s[i] = 0.0f; dp[i] = 0.0f; }
-#pragma unroll
-                for (int kk = 0; kk < 8; ++kk) s = mfma32(read_rows(sK, kb * 32, kk, l32, g), qf[kk], s);
-#pragma unroll
-                for (int kk = 0; kk < 8; ++kk) dp = mfma32(read_rows(sV, kb * 32, kk, l32, g), gf[kk], dp);
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int j = j0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-                    const float pr = j <= lim ? fast_exp2(s[i] * c2 - lse2) : 0.0f;
-                    s[i] = pr * (dp[i] - Dq);
-                }
-#pragma unroll
-                for (int hh = 0; hh < 2; ++hh) {
-                    const bf16x8 dsf = pack8(s, 8 * hh);
-#pragma unroll
-                    for (int db = 0; db < 4; ++db)
-                        dq[db] = mfma32(read_cols(sK, kb * 32 + hh * 16, db, lane), dsf, dq[db]);
-                }
-            }
-        }
+        LRSA_DQ_TILE(sK0, sV0, tile * DQ_BN);
+        if (tile + 1 >= ntiles) break;
+        wait_vmcnt<0>();
         __syncthreads();
+        if (tile + 2 < ntiles) {
+            issue(sK0, sV0);
+            if (tile + 3 < ntiles) fetch_pos(tile + 3);
+        }
+        LRSA_DQ_TILE(sK1, sV1, (tile + 1) * DQ_BN);
     }
-#undef LRSA_POS
-#undef LRSA_FETCH_POS
-#undef LRSA_LD
-#undef LRSA_ISSUE
-#undef LRSA_ST
-#undef LRSA_STASH
+
+#undef LRSA_DQ_TILE
 
     if (tq <= t_last) {
         bf16_t* orow = dQ + b * D.qs[0] + hq * D.qs[1] + int64_t(tq) * D.qs[2];
@@ -220,8 +270,88 @@ __device__ __forceinline__ int first_chunk_seeing(const Dims& D, int j0) {
     return j0 < D.S ? 0 : (j0 - D.S) / D.K + D.lp + 1;
 }
 
-template <bool GATHER>
-__global__ __launch_bounds__(BWD_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t* __restrict__ Q,
+// One step (32 query rows) of the key-outer walk for one wave.  sLD holds this wave's copy of the
+// rows' lse (floats 0..31) and D (floats 32..63).  r0 = first row of the step; rows >= tb are padding.
+// lim_u: GATHER with chunk-aligned steps: the largest gather-list entry the step's chunk sees.
+template <bool GATHER, bool UNIFORM, bool MASK>
+__device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ, const unsigned char* sG,
+                                         const float* sLD, const bf16x8 (&kf)[8], const bf16x8 (&vf)[8],
+                                         const LaneOffs& lo, f32x16 (&dk)[4], f32x16 (&dv)[4], int r0, int tb,
+                                         int kcmp, int lim_u, float c2, int lane) {
+    const int g = lane >> 5;
+    f32x16 s, dp;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { s[i] = 0.0f; dp[i] = 0.0f; }
+    // operands are read four ahead of the MFMAs that consume them (K/V fragments and the accumulators
+    // leave room for no more)
+    bf16x8 a[4], ga[4], qa[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) a[kk] = read_rows_o(sQ, lo, 0, kk);
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        s = mfma32(a[kk & 3], kf[kk], s);
+        a[kk & 3] = kk < 4 ? read_rows_o(sQ, lo, 0, kk + 4) : read_rows_o(sG, lo, 0, kk - 4);
+    }
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        dp = mfma32(a[kk & 3], vf[kk], dp);
+        if (kk < 4) a[kk & 3] = read_rows_o(sG, lo, 0, kk + 4);
+        else ga[kk - 4] = read_cols_o(sG, lo, 0, kk - 4);
+    }
+#pragma unroll
+    for (int db = 0; db < 4; ++db) qa[db] = read_cols_o(sQ, lo, 0, db);
+#pragma unroll
+    for (int a4 = 0; a4 < 4; ++a4) {
+        const int rb = 8 * a4 + 4 * g;
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(sLD + rb);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(sLD + 32 + rb);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int i = a4 * 4 + r;
+            float pr = fast_exp2(__builtin_fmaf(s[i], c2, l4[r] * -1.4426950408889634f));
+            if (MASK) {
+                const int t = r0 + rb + r;
+                int lim;  // largest key id row t sees
+                if (!GATHER) lim = t;
+                else if (UNIFORM) lim = lim_u;
+                else lim = gather_count(D, (t - D.S) / D.L) - 1;
+                if (t >= tb) lim = -1;
+                pr = kcmp <= lim ? pr : 0.0f;
+            }
+            s[i] = pr;
+            dp[i] = pr * (dp[i] - d4[r]);
+        }
+    }
+    bf16x8 gb[4], qb[4];
+    {
+        const bf16x8 pf = pack8(s, 0);
+        const bf16x8 dsf = pack8(dp, 0);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            dv[db] = mfma32(ga[db], pf, dv[db]);
+            gb[db] = read_cols_o(sG, lo, 16, db);
+        }
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            dk[db] = mfma32(qa[db], dsf, dk[db]);
+            qb[db] = read_cols_o(sQ, lo, 16, db);
+        }
+    }
+    {
+        const bf16x8 pf = pack8(s, 8);
+        const bf16x8 dsf = pack8(dp, 8);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) dv[db] = mfma32(gb[db], pf, dv[db]);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) dk[db] = mfma32(qb[db], dsf, dk[db]);
+    }
+}
+
+constexpr int KV_STAGES = 4;
+constexpr int KV_LOADS_PER_STEP = 5;   // asynchronous copies one wave issues per step: 2 Q, 2 dO, 1 lse|D
+
+template <bool GATHER, bool UNIFORM>
+__global__ __launch_bounds__(BWD_THREADS, 1) void k_bwd_dkv(Dims D, const bf16_t* __restrict__ Q,
                                                              const bf16_t* __restrict__ K,
                                                              const bf16_t* __restrict__ V,
                                                              const bf16_t* __restrict__ dO,
@@ -230,11 +360,13 @@ __global__ __launch_bounds__(BWD_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t
                                                              const int32_t* __restrict__ idx,
                                                              bf16_t* __restrict__ dK, bf16_t* __restrict__ dV,
                                                              float* __restrict__ part, BwdPlan P) {
-    __shared__ __attribute__((aligned(16))) unsigned char sQ[KV_BQ * TILE_ROW_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char sG[KV_BQ * TILE_ROW_BYTES];
-    __shared__ __attribute__((aligned(16))) float sL[KV_BQ];   // lse in log2 units
-    __shared__ __attribute__((aligned(16))) float sD[KV_BQ];   // D
-    __shared__ __attribute__((aligned(16))) int sLim[KV_BQ];   // largest key id the row sees (-1: none)
+    // four stages of (Q rows, dO rows, per-wave lse|D); separate arrays so that reads of one stage
+    // need not wait for the asynchronous fill of another
+    __shared__ __attribute__((aligned(16))) unsigned char sQ0[KV_BQ * TILE_ROW_BYTES], sQ1[KV_BQ * TILE_ROW_BYTES],
+        sQ2[KV_BQ * TILE_ROW_BYTES], sQ3[KV_BQ * TILE_ROW_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sG0[KV_BQ * TILE_ROW_BYTES], sG1[KV_BQ * TILE_ROW_BYTES],
+        sG2[KV_BQ * TILE_ROW_BYTES], sG3[KV_BQ * TILE_ROW_BYTES];
+    __shared__ __attribute__((aligned(16))) float sL0[4 * 64], sL1[4 * 64], sL2[4 * 64], sL3[4 * 64];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
@@ -246,8 +378,10 @@ __global__ __launch_bounds__(BWD_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t
     int ta, tb;          // query rows [ta, tb) of every head of the group
     int slice = 0;
     if (GATHER) {
-        const int jt = blockIdx.x / P.nsl;
-        slice = blockIdx.x % P.nsl;
+        // consecutive workgroups take consecutive list tiles of ONE query slice, so the Q and dO rows
+        // they stream at the same time are the same rows (shared through L2 and the memory-side cache)
+        const int jt = blockIdx.x % P.gtiles;
+        slice = blockIdx.x / P.gtiles;
         key0 = jt * KV_BK;
         key_end = P.gl_total;
         const int qa = first_chunk_seeing(D, key0) + slice * P.qch;
@@ -294,41 +428,30 @@ __global__ __launch_bounds__(BWD_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t
         }
     }
     const int wave_key0 = key0 + wave * 32;
+    const bool wave_keys_valid = wave_key0 + 31 < key_end;
+    const LaneOffs lo = make_lane_offs(lane);
 
-    // ---- loader: thread takes row tid/8 of the step, chunks 2*(tid%8) and +1 of Q and dO
-    const int lrow = tid >> 3, lc = (tid & 7) * 2;
-    uint4 q0, q1, g0, g1;
-    float r_l = 0.0f, r_d = 0.0f;
-    int r_lim = -1;
-#define LRSA_ISSUE(step)                                                                              \
-    {                                                                                                 \
-        const int gi_ = (step) / sph, r0_ = ta + ((step) % sph) * KV_BQ;                              \
-        const int t_ = min(r0_ + lrow, tb - 1);                                                       \
-        const int hq_ = h * D.G + gi_;                                                                \
-        const int64_t off_ = b * D.qs[0] + hq_ * D.qs[1] + int64_t(t_) * D.qs[2] + lc * 8;             \
-        q0 = *reinterpret_cast<const uint4*>(Q + off_);                                               \
-        q1 = *reinterpret_cast<const uint4*>(Q + off_ + 8);                                           \
-        g0 = *reinterpret_cast<const uint4*>(dO + off_);                                              \
-        g1 = *reinterpret_cast<const uint4*>(dO + off_ + 8);                                          \
-        if (tid < KV_BQ) {                                                                            \
-            const int tt_ = r0_ + tid;                                                                \
-            const int tc_ = min(tt_, tb - 1);                                                         \
-            const int64_t rid_ = (int64_t(b) * D.Hq + hq_) * D.n + tc_;                               \
-            r_l = lse[rid_] * 1.4426950408889634f;                                                    \
-            r_d = Dsum[rid_];                                                                         \
-            if (tt_ >= tb) r_lim = -1;                                                                \
-            else if (GATHER) r_lim = gather_count(D, (tt_ - D.S) / D.L) - 1;                          \
-            else r_lim = tt_;                                                                         \
-        }                                                                                             \
-    }
-#define LRSA_STASH()                                                                                  \
-    {                                                                                                 \
-        *reinterpret_cast<uint4*>(sQ + tile_off(lrow, lc)) = q0;                                      \
-        *reinterpret_cast<uint4*>(sQ + tile_off(lrow, lc + 1)) = q1;                                  \
-        *reinterpret_cast<uint4*>(sG + tile_off(lrow, lc)) = g0;                                      \
-        *reinterpret_cast<uint4*>(sG + tile_off(lrow, lc + 1)) = g1;                                  \
-        if (tid < KV_BQ) { sL[tid] = r_l; sD[tid] = r_d; sLim[tid] = r_lim; }                         \
-    }
+    // ---- loader: wave w fills rows 8w .. 8w+7 of the Q and dO tiles (two copies of 4 rows each) and
+    // its own lse|D block.  Steps past the end repeat the last one so that every wave always has the
+    // same number of copies in flight.
+    auto issue = [&](int step, unsigned char* sQ, unsigned char* sG, float* sL) {
+        const int sc = step < nsteps ? step : nsteps - 1;
+        const int gi = sc / sph, r0 = ta + (sc % sph) * KV_BQ;
+        const int hq = h * D.G + gi;
+        const int64_t base = b * D.qs[0] + hq * D.qs[1];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int r4 = 8 * wave + 4 * i;
+            const int row = async_row(r4, lane);
+            const int t = min(r0 + row, tb - 1);
+            const int64_t off = base + int64_t(t) * D.qs[2] + async_chunk(row, lane) * 8;
+            async_rows4(Q + off, sQ, r4);
+            async_rows4(dO + off, sG, r4);
+        }
+        const int t = min(r0 + l32, tb - 1);
+        const float* src = (g ? Dsum : lse) + (int64_t(b) * D.Hq + hq) * D.n + t;
+        __builtin_amdgcn_global_load_lds((gbl_void_t*)src, (lds_void_t*)(sL + wave * 64), 4, 0, 0);
+    };
 
     const float c2 = D.scale * 1.4426950408889634f;
     f32x16 dk[4], dv[4];
@@ -337,51 +460,37 @@ __global__ __launch_bounds__(BWD_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t
 #pragma unroll
         for (int i = 0; i < 16; ++i) { dk[db][i] = 0.0f; dv[db][i] = 0.0f; }
 
-    LRSA_ISSUE(0);
-    for (int step = 0; step < nsteps; ++step) {
-        LRSA_STASH();
-        __syncthreads();
-        if (step + 1 < nsteps) LRSA_ISSUE(step + 1);
-        const int r0 = ta + (step % sph) * KV_BQ;
-        // WINDOW: rows before the wave's first key see none of its keys
-        if (GATHER || r0 + KV_BQ - 1 >= wave_key0) {
-            f32x16 s, dp;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) { s[i] = 0.0f; dp[i] = 0.0f; }
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) s = mfma32(read_rows(sQ, 0, kk, l32, g), kf[kk], s);
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) dp = mfma32(read_rows(sG, 0, kk, l32, g), vf[kk], dp);
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const int rb = 8 * a + 4 * g;
-                const f32x4 l4 = *reinterpret_cast<const f32x4*>(sL + rb);
-                const f32x4 d4 = *reinterpret_cast<const f32x4*>(sD + rb);
-                const int4 m4 = *reinterpret_cast<const int4*>(sLim + rb);
-                const int lims[4] = {m4.x, m4.y, m4.z, m4.w};
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int i = a * 4 + r;
-                    const float pr = kcmp <= lims[r] ? fast_exp2(s[i] * c2 - l4[r]) : 0.0f;
-                    s[i] = pr;
-                    dp[i] = pr * (dp[i] - d4[r]);
-                }
-            }
-#pragma unroll
-            for (int hh = 0; hh < 2; ++hh) {
-                const bf16x8 pf = pack8(s, 8 * hh);
-                const bf16x8 dsf = pack8(dp, 8 * hh);
-#pragma unroll
-                for (int db = 0; db < 4; ++db) {
-                    dv[db] = mfma32(read_cols(sG, hh * 16, db, lane), pf, dv[db]);
-                    dk[db] = mfma32(read_cols(sQ, hh * 16, db, lane), dsf, dk[db]);
-                }
-            }
-        }
-        __syncthreads();
+#define LRSA_KV_STEP(step, sQ, sG, sL, sQn, sGn, sLn)                                                   \
+    {                                                                                                    \
+        wait_vmcnt<(KV_STAGES - 2) * KV_LOADS_PER_STEP>(); /* this wave's copies for `step` landed */   \
+        __syncthreads();                                     /* everybody's did; stage of step-1 free */ \
+        issue((step) + KV_STAGES - 1, sQn, sGn, sLn);                                                    \
+        const int r0_ = ta + ((step) % sph) * KV_BQ;                                                     \
+        int lim_u_ = 0;                                                                                  \
+        if (GATHER && UNIFORM) lim_u_ = gather_count(D, (r0_ - D.S) / D.L) - 1;                          \
+        /* every (row, key) pair of the step visible for this wave? */                                   \
+        const bool full_ = wave_keys_valid && r0_ + KV_BQ <= tb &&                                       \
+                           (GATHER ? (UNIFORM && lim_u_ >= wave_key0 + 31) : (r0_ >= wave_key0 + 31));   \
+        if (full_)                                                                                       \
+            dkv_step<GATHER, UNIFORM, false>(D, sQ, sG, sL + wave * 64, kf, vf, lo, dk, dv, r0_, tb, kcmp, lim_u_, c2, lane); \
+        else if (GATHER || r0_ + KV_BQ - 1 >= wave_key0) /* WINDOW: earlier rows see none of the wave's keys */ \
+            dkv_step<GATHER, UNIFORM, true>(D, sQ, sG, sL + wave * 64, kf, vf, lo, dk, dv, r0_, tb, kcmp, lim_u_, c2, lane); \
     }
-#undef LRSA_ISSUE
-#undef LRSA_STASH
+
+    issue(0, sQ0, sG0, sL0);
+    issue(1, sQ1, sG1, sL1);
+    issue(2, sQ2, sG2, sL2);
+    for (int step = 0; step < nsteps; step += 4) {
+        LRSA_KV_STEP(step, sQ0, sG0, sL0, sQ3, sG3, sL3);
+        if (step + 1 >= nsteps) break;
+        LRSA_KV_STEP(step + 1, sQ1, sG1, sL1, sQ0, sG0, sL0);
+        if (step + 2 >= nsteps) break;
+        LRSA_KV_STEP(step + 2, sQ2, sG2, sL2, sQ1, sG1, sL1);
+        if (step + 3 >= nsteps) break;
+        LRSA_KV_STEP(step + 3, sQ3, sG3, sL3, sQ2, sG2, sL2);
+    }
+#undef LRSA_KV_STEP
+    wait_vmcnt<0>();   // drain the copies issued past the end before the workgroup's LDS is released
 
     if (!kvalid) return;
     const size_t part_stride = size_t(D.B) * D.Hkv * P.gl_total * 128;   // floats per slice
@@ -462,12 +571,19 @@ hipError_t launch_attn_bwd_mfma(const Dims& D, const void* Q, const void* K, con
         LRSA_TIMED_LAUNCH("k_bwd_dq", st, k_bwd_dq, dim3(qtiles, D.Hq, D.B), dim3(BWD_THREADS), 0, st, D, q, k, v, g, lse, Dsum, idx,
                            (bf16_t*)dQ, P.sink_tiles_q, P.tpc_q);
     if (P.gtiles > 0)
-        LRSA_TIMED_LAUNCH("k_bwd_dkvtrue", st, k_bwd_dkv<true>, dim3(P.gtiles * P.nsl, D.Hkv, D.B), dim3(BWD_THREADS), 0, st, D, q, k, v,
-                           g, lse, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
+    {
+        // steps of 32 rows stay inside one query chunk when the lag is a multiple of 32
+        if (D.L % KV_BQ == 0)
+            LRSA_TIMED_LAUNCH("k_bwd_dkv_gather", st, (k_bwd_dkv<true, true>), dim3(P.gtiles * P.nsl, D.Hkv, D.B),
+                              dim3(BWD_THREADS), 0, st, D, q, k, v, g, lse, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
+        else
+            LRSA_TIMED_LAUNCH("k_bwd_dkv_gather", st, (k_bwd_dkv<true, false>), dim3(P.gtiles * P.nsl, D.Hkv, D.B),
+                              dim3(BWD_THREADS), 0, st, D, q, k, v, g, lse, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
+    }
     const int ktiles = P.sink_tiles_k + D.nq * P.tpc_k;
     if (ktiles > 0)
-        LRSA_TIMED_LAUNCH("k_bwd_dkvfalse", st, k_bwd_dkv<false>, dim3(ktiles, D.Hkv, D.B), dim3(BWD_THREADS), 0, st, D, q, k, v, g, lse,
-                           Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
+        LRSA_TIMED_LAUNCH("k_bwd_dkv_window", st, (k_bwd_dkv<false, true>), dim3(ktiles, D.Hkv, D.B), dim3(BWD_THREADS), 0,
+                          st, D, q, k, v, g, lse, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
     return hipGetLastError();
 }
 

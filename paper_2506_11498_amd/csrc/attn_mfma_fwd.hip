@@ -6,8 +6,8 @@
 // stream: the gather list (sink, then the survivors of the compressed chunks) followed by the
 // contiguous local window up to the query itself.  Stream entry j is visible to query t iff
 // j <= ng + t - cs, so only the last tiles need a mask.  The stream is walked in tiles of 64
-// keys; K and V rows of a tile are fetched (gathered by position) into registers one tile
-// ahead and staged row-major in LDS.
+// keys; K and V rows of a tile are copied (gathered by position) asynchronously from global
+// memory straight into a two-stage LDS ring, one tile ahead, row-major and swizzled.
 //
 // Per tile and wave:  S^T = K Q^T  (keys x queries, so a lane owns one query column and the
 // softmax statistics are per lane), P^T = exp2(S^T - m), O^T += V^T P^T with the accumulator
@@ -24,14 +24,114 @@ constexpr int FWD_THREADS = 256;
 bool mfma_supported(const Dims& D) { return D.dtype == 1 && D.d == 128; }
 size_t attn_fwd_mfma_ws_bytes(const Dims&) { return 0; }
 
+// One 64-key tile of the walk for one wave: S^T = K Q^T, masked online softmax, O^T += V^T P^T.
+struct FwdState {
+    float m_run, l_run;
+    f32x16 o[4];
+};
+
+// MASK: the tile holds entries some query of the wave does not see (only the last tiles of a walk).
+// The running maximum is refreshed lazily: as long as no query's tile maximum exceeds its reference
+// by more than 2^8, the old reference is kept (probabilities stay below 256, exact enough in fp32 sums
+// and bf16 operands) and the accumulators need no rescaling.
+template <bool MASK>
+__device__ __forceinline__ void fwd_tile(const unsigned char* sK, const unsigned char* sV, const bf16x8 (&qf)[8],
+                                         const LaneOffs& lo, FwdState& st, int j0, int lim, int wave_lim_max,
+                                         float c2, int lane) {
+    const int g = lane >> 5;
+    // MASK tiles: do the second 32 keys hold a visible key for some query of the wave?
+    const bool two = !MASK || j0 + 32 <= wave_lim_max;
+    f32x16 s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[kb][i] = 0.0f;
+    // S^T = K Q^T: operands are read a block of 8 ahead of the MFMAs that consume them
+    {
+        bf16x8 a[8];
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) a[kk] = read_rows_o(sK, lo, 0, kk);
+        if (two) {
+            bf16x8 a1[8];
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                s[0] = mfma32(a[kk], qf[kk], s[0]);
+                a1[kk] = read_rows_o(sK, lo, 32, kk);
+            }
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) s[1] = mfma32(a1[kk], qf[kk], s[1]);
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) s[0] = mfma32(a[kk], qf[kk], s[0]);
+        }
+    }
+    // first V^T operands are fetched while the softmax runs
+    bf16x8 va[4], vb[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db) va[db] = read_cols_o(sV, lo, 0, db);
+    float mx = -INFINITY;   // raw (unscaled) tile maximum of this lane's query
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            if (MASK) {
+                const int j = j0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+                s[kb][i] = j <= lim ? s[kb][i] : -INFINITY;
+            }
+            mx = fmaxf(mx, s[kb][i]);
+        }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c2;
+    if (__builtin_amdgcn_ballot_w64(mx > st.m_run + 8.0f) != 0) {   // wave-uniform; always taken on the first tile
+        const float m_new = fmaxf(st.m_run, mx);   // finite: the first tile holds a visible key for every query
+        const float corr = fast_exp2(st.m_run - m_new);
+        st.l_run *= corr;
+        st.m_run = m_new;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) st.o[db][i] *= corr;
+    }
+    const float neg_m = -st.m_run;
+    float psum = 0.0f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float pv = fast_exp2(__builtin_fmaf(s[kb][i], c2, neg_m));
+            s[kb][i] = pv;
+            psum += pv;
+        }
+    st.l_run += psum;
+    // O^T += V^T P^T, 16 keys at a time; the operands of the next 16 keys are read during the MFMAs
+#define LRSA_PV(kg, cur, nxt)                                                          \
+    {                                                                                  \
+        const bf16x8 pf = pack8(s[(kg) >> 1], 8 * ((kg) & 1));                         \
+        _Pragma("unroll") for (int db = 0; db < 4; ++db) {                             \
+            st.o[db] = mfma32(cur[db], pf, st.o[db]);                                  \
+            if ((kg) + 1 < 4) nxt[db] = read_cols_o(sV, lo, ((kg) + 1) * 16, db);      \
+        }                                                                              \
+    }
+    LRSA_PV(0, va, vb);
+    LRSA_PV(1, vb, va);
+    if (two) {
+        LRSA_PV(2, va, vb);
+        LRSA_PV(3, vb, va);
+    }
+#undef LRSA_PV
+}
+
 __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_t* __restrict__ Q,
                                                               const bf16_t* __restrict__ K,
                                                               const bf16_t* __restrict__ V,
                                                               const int32_t* __restrict__ idx,
                                                               bf16_t* __restrict__ O, float* __restrict__ lse,
                                                               int sink_tiles, int tpc) {
-    __shared__ __attribute__((aligned(16))) unsigned char sK[FWD_BN * TILE_ROW_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char sV[FWD_BN * TILE_ROW_BYTES];
+    // two stages of (K tile, V tile); separate arrays so that reads of one stage need not wait for
+    // the asynchronous fill of the other
+    __shared__ __attribute__((aligned(16))) unsigned char sK0[FWD_BN * TILE_ROW_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sV0[FWD_BN * TILE_ROW_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sK1[FWD_BN * TILE_ROW_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sV1[FWD_BN * TILE_ROW_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
@@ -68,106 +168,71 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + kk * 16 + g * 8);
     }
-    const int lim = ng + tq - cs;                                   // last stream entry this query sees
-    const int wave_first = t0 + wave * 32;
-    const int wave_lim_min = ng + wave_first - cs;                  // ... the wave's first query sees
-    const int wave_lim_max = ng + min(wave_first + 31, t_last) - cs;  // ... its last valid query sees
+    const int lim = ng + tq - cs;                                     // last stream entry this query sees
+    const int wave_lim_max = ng + min(t0 + wave * 32 + 31, t_last) - cs;  // ... the wave's last valid query sees
 
-    // loader mapping: thread takes tile rows 4*kg4 .. +3, 16-byte chunk c16 of K and of V
-    const int kg4 = tid >> 4, c16 = tid & 15;
-    int pos0, pos1, pos2, pos3;
-    uint4 kr0, kr1, kr2, kr3, vr0, vr1, vr2, vr3;
-    // rows past the stream end re-read its last key; they are masked
-#define LRSA_POS(tile, e) stream_pos(D, idx_h, min((tile) * FWD_BN + 4 * kg4 + (e), m_max - 1), ng, cs)
-#define LRSA_FETCH_POS(tile) { pos0 = LRSA_POS(tile, 0); pos1 = LRSA_POS(tile, 1); pos2 = LRSA_POS(tile, 2); pos3 = LRSA_POS(tile, 3); }
-#define LRSA_LD(base, p) (*reinterpret_cast<const uint4*>((base) + int64_t(p) * D.ks[2] + c16 * 8))
-#define LRSA_ISSUE() { kr0 = LRSA_LD(Kh, pos0); kr1 = LRSA_LD(Kh, pos1); kr2 = LRSA_LD(Kh, pos2); kr3 = LRSA_LD(Kh, pos3); \
-                       vr0 = LRSA_LD(Vh, pos0); vr1 = LRSA_LD(Vh, pos1); vr2 = LRSA_LD(Vh, pos2); vr3 = LRSA_LD(Vh, pos3); }
-#define LRSA_ST(tile_base, e, v) (*reinterpret_cast<uint4*>((tile_base) + tile_off(4 * kg4 + (e), c16)) = (v))
-#define LRSA_STASH() { LRSA_ST(sK, 0, kr0); LRSA_ST(sK, 1, kr1); LRSA_ST(sK, 2, kr2); LRSA_ST(sK, 3, kr3); \
-                       LRSA_ST(sV, 0, vr0); LRSA_ST(sV, 1, vr1); LRSA_ST(sV, 2, vr2); LRSA_ST(sV, 3, vr3); }
+    // loader: wave w fills tile rows 16w .. 16w+15 with four asynchronous copies of 4 rows each;
+    // rows past the stream end re-read its last key and are masked
+    int pos[4];
+    auto fetch_pos = [&](int tile) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int j = tile * FWD_BN + async_row(16 * wave + 4 * i, lane);
+            pos[i] = stream_pos(D, idx_h, j < m_max ? j : m_max - 1, ng, cs);
+        }
+    };
+    auto issue = [&](unsigned char* sK, unsigned char* sV) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r4 = 16 * wave + 4 * i;
+            const int64_t off = int64_t(pos[i]) * D.ks[2] + async_chunk(async_row(r4, lane), lane) * 8;
+            async_rows4(Kh + off, sK, r4);
+            async_rows4(Vh + off, sV, r4);
+        }
+    };
 
     const float c2 = D.scale * 1.4426950408889634f;  // logits are kept in log2 units
-    float m_run = -INFINITY, l_run = 0.0f;
-    f32x16 o[4];
+    const LaneOffs lo = make_lane_offs(lane);
+    FwdState st;
+    st.m_run = -INFINITY;
+    st.l_run = 0.0f;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][i] = 0.0f;
+        for (int i = 0; i < 16; ++i) st.o[db][i] = 0.0f;
 
-    LRSA_FETCH_POS(0);
-    LRSA_ISSUE();
-    if (ntiles > 1) LRSA_FETCH_POS(1);
-    for (int tile = 0; tile < ntiles; ++tile) {
-        LRSA_STASH();
-        __syncthreads();
-        if (tile + 1 < ntiles) {
-            LRSA_ISSUE();
-            if (tile + 2 < ntiles) LRSA_FETCH_POS(tile + 2);
-        }
-        const int j0 = tile * FWD_BN;
-        if (j0 <= wave_lim_max) {  // otherwise every key of the tile is masked for this wave
-            f32x16 s[2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) s[kb][i] = 0.0f;
-#pragma unroll
-                for (int kk = 0; kk < 8; ++kk) s[kb] = mfma32(read_rows(sK, kb * 32, kk, l32, g), qf[kk], s[kb]);
-            }
-            float mx = -INFINITY;
-            if (j0 + FWD_BN - 1 > wave_lim_min) {
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int j = j0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-                        const float v = j <= lim ? s[kb][i] * c2 : -INFINITY;
-                        s[kb][i] = v;
-                        mx = fmaxf(mx, v);
-                    }
-            } else {
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float v = s[kb][i] * c2;
-                        s[kb][i] = v;
-                        mx = fmaxf(mx, v);
-                    }
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run, mx);   // finite: the first tile holds a visible key for every query
-            const float corr = fast_exp2(m_run - m_new);
-            float psum = 0.0f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float pv = fast_exp2(s[kb][i] - m_new);
-                    s[kb][i] = pv;
-                    psum += pv;
-                }
-            l_run = l_run * corr + psum;
-            m_run = m_new;
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) o[db][i] *= corr;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int hh = 0; hh < 2; ++hh) {
-                    const bf16x8 pf = pack8(s[kb], 8 * hh);
-#pragma unroll
-                    for (int db = 0; db < 4; ++db)
-                        o[db] = mfma32(read_cols(sV, kb * 32 + hh * 16, db, lane), pf, o[db]);
-                }
-        }
-        __syncthreads();
+    const int wave_lim_min = ng + t0 + wave * 32 - cs;   // last stream entry the wave's first query sees
+#define LRSA_FWD_TILE(sK, sV, j0_)                                                                   \
+    {                                                                                                \
+        const int j0 = (j0_);                                                                        \
+        if (j0 + FWD_BN - 1 <= wave_lim_min) fwd_tile<false>(sK, sV, qf, lo, st, j0, lim, wave_lim_max, c2, lane); \
+        else if (j0 <= wave_lim_max) fwd_tile<true>(sK, sV, qf, lo, st, j0, lim, wave_lim_max, c2, lane);          \
     }
 
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    fetch_pos(0);
+    issue(sK0, sV0);
+    if (ntiles > 1) fetch_pos(1);
+    for (int tile = 0; tile < ntiles; tile += 2) {
+        wait_vmcnt<0>();      // this wave's copies for `tile` have landed (and the next positions are here)
+        __syncthreads();      // ... everybody's have, and everybody is done with the other stage
+        if (tile + 1 < ntiles) {
+            issue(sK1, sV1);
+            if (tile + 2 < ntiles) fetch_pos(tile + 2);
+        }
+        LRSA_FWD_TILE(sK0, sV0, tile * FWD_BN);
+        if (tile + 1 >= ntiles) break;
+        wait_vmcnt<0>();
+        __syncthreads();
+        if (tile + 2 < ntiles) {
+            issue(sK0, sV0);
+            if (tile + 3 < ntiles) fetch_pos(tile + 3);
+        }
+        LRSA_FWD_TILE(sK1, sV1, (tile + 1) * FWD_BN);
+    }
+
+#undef LRSA_FWD_TILE
+
+    const float l_tot = st.l_run + __shfl_xor(st.l_run, 32, 64);
     if (tq <= t_last) {
         const float inv = 1.0f / l_tot;
         bf16_t* orow = O + b * D.qs[0] + hq * D.qs[1] + int64_t(tq) * D.qs[2];
@@ -177,11 +242,11 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
             for (int a = 0; a < 4; ++a) {
                 f32x4 v;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) v[r] = o[db][a * 4 + r] * inv;
+                for (int r = 0; r < 4; ++r) v[r] = st.o[db][a * 4 + r] * inv;
                 const bf16x4 pk = __builtin_convertvector(v, bf16x4);
                 *reinterpret_cast<bf16x4*>(orow + db * 32 + a * 8 + g * 4) = pk;
             }
-        if (g == 0) lse[(int64_t(b) * D.Hq + hq) * D.n + tq] = (m_run + __builtin_log2f(l_tot)) * 0.6931471805599453f;
+        if (g == 0) lse[(int64_t(b) * D.Hq + hq) * D.n + tq] = (st.m_run + __builtin_log2f(l_tot)) * 0.6931471805599453f;
     }
 }
 

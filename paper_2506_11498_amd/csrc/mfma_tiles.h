@@ -59,6 +59,39 @@ __device__ __forceinline__ bf16x8 read_cols(const unsigned char* tile, int rb16,
     return u.v;
 }
 
+// Per-lane byte offsets of the two read patterns inside a tile, computed once: the swizzle only looks
+// at the low four bits of the row, so other row blocks (multiples of 16 rows) are immediates on top.
+struct LaneOffs {
+    int row[8];      // read_rows: row l32, channel block kk
+    int col[4][2];   // read_cols: channel block db, first / second transposing read
+};
+__device__ __forceinline__ LaneOffs make_lane_offs(int lane) {
+    LaneOffs o;
+    const int l32 = lane & 31, g = lane >> 5, lam = lane & 15, m = (lane >> 4) & 1;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) o.row[kk] = tile_off(l32, kk * 2 + g);
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+        const int ch = db * 32 + 16 * m + 4 * (lam & 3);
+#pragma unroll
+        for (int jh = 0; jh < 2; ++jh) o.col[db][jh] = tile_off(4 * g + (lam >> 2) + 8 * jh, ch >> 3) + (ch & 7) * 2;
+    }
+    return o;
+}
+// same operands as read_rows / read_cols, from the precomputed offsets; rb is a multiple of 32, rb16 of 16
+__device__ __forceinline__ bf16x8 read_rows_o(const unsigned char* tile, const LaneOffs& o, int rb, int kk) {
+    return *reinterpret_cast<const bf16x8*>(tile + o.row[kk] + rb * TILE_ROW_BYTES);
+}
+__device__ __forceinline__ bf16x8 read_cols_o(const unsigned char* tile, const LaneOffs& o, int rb16, int db) {
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(tile + o.col[db][0] + rb16 * TILE_ROW_BYTES));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(tile + o.col[db][1] + rb16 * TILE_ROW_BYTES));
+    union { s16x4 h[2]; bf16x8 v; } u;
+    u.h[0] = lo;
+    u.h[1] = hi;
+    return u.v;
+}
+
 // registers i0 .. i0+7 of a C-layout accumulator as a bf16 operand
 __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int i0) {
     f32x8 t;
@@ -68,6 +101,28 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int i0) {
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ---- asynchronous global -> LDS copies (global_load_lds_dwordx4) --------------------------------
+// One wave instruction moves 64 x 16 bytes: lane l's 16 bytes land at lds_base + 16*l (checked on the
+// hardware), i.e. four consecutive 256-byte tile rows starting at row r4.  The swizzle is applied on
+// the global side: the lane whose slot is physical chunk pc of row r fetches logical chunk pc ^ swz(r).
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void gbl_void_t;
+
+// tile row and 16-byte logical chunk this lane fetches when its wave fills rows r4 .. r4+3
+__device__ __forceinline__ int async_row(int r4, int lane) { return r4 + (lane >> 4); }
+__device__ __forceinline__ int async_chunk(int row, int lane) { return (lane & 15) ^ swz(row); }
+
+// src: this lane's 16 bytes in global memory; tile: LDS tile base; r4: first of the 4 rows (wave-uniform)
+__device__ __forceinline__ void async_rows4(const void* src, unsigned char* tile, int r4) {
+    __builtin_amdgcn_global_load_lds((gbl_void_t*)src, (lds_void_t*)(tile + r4 * TILE_ROW_BYTES), 16, 0, 0);
+}
+
+// s_waitcnt vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14; expcnt, lgkmcnt left open)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
 
 // position of stream entry j: the gather list (sink positions, then the flattened survivor
 // lists) followed by the contiguous window that starts at cs
