@@ -22,7 +22,8 @@ namespace lrsa {
 
 constexpr int BWD_THREADS = 256;
 constexpr int DQ_BM = 128, DQ_BN = 64;
-constexpr int KV_BK = 128;  // keys per workgroup (32 per wave)
+constexpr int KV_NB = 2;              // 32-key blocks per wave
+constexpr int KV_BK = 128 * KV_NB;   // keys per workgroup (32*KV_NB per wave)
 constexpr int KV_BQ = 32;   // query rows per step
 constexpr int KV_MAX_SLICES = 8;
 
@@ -275,76 +276,106 @@ __device__ __forceinline__ int first_chunk_seeing(const Dims& D, int j0) {
 // lim_u: GATHER with chunk-aligned steps: the largest gather-list entry the step's chunk sees.
 template <bool GATHER, bool UNIFORM, bool MASK>
 __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ, const unsigned char* sG,
-                                         const float* sLD, const bf16x8 (&kf)[8], const bf16x8 (&vf)[8],
-                                         const LaneOffs& lo, f32x16 (&dk)[4], f32x16 (&dv)[4], int r0, int tb,
-                                         int kcmp, int lim_u, float c2, int lane) {
+                                         const float* sLD, const bf16x8 (&kf)[KV_NB][8], const bf16x8 (&vf)[KV_NB][8],
+                                         const LaneOffs& lo, f32x16 (&dk)[KV_NB][4], f32x16 (&dv)[KV_NB][4], int r0,
+                                         int tb, const int (&kcmp)[KV_NB], int lim_u, float c2, int lane) {
     const int g = lane >> 5;
-    f32x16 s, dp;
+    // every operand read from LDS feeds KV_NB MFMAs; operands are read four ahead of their use.
+    // The scheduling barriers keep the phases apart: without them the operand reads of later phases
+    // are hoisted over earlier ones and the register file (K, V fragments + accumulators) overflows.
+    bf16x8 a[4];
+    bf16x8 pf[KV_NB][2];   // A = exp(S - lse) as bf16 operands, 16 rows each
+    {
+        f32x16 s[KV_NB];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { s[i] = 0.0f; dp[i] = 0.0f; }
-    // operands are read four ahead of the MFMAs that consume them (K/V fragments and the accumulators
-    // leave room for no more)
-    bf16x8 a[4], ga[4], qa[4];
+        for (int nb = 0; nb < KV_NB; ++nb)
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) a[kk] = read_rows_o(sQ, lo, 0, kk);
+            for (int i = 0; i < 16; ++i) s[nb][i] = 0.0f;
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-        s = mfma32(a[kk & 3], kf[kk], s);
-        a[kk & 3] = kk < 4 ? read_rows_o(sQ, lo, 0, kk + 4) : read_rows_o(sG, lo, 0, kk - 4);
-    }
+        for (int kk = 0; kk < 4; ++kk) a[kk] = read_rows_o(sQ, lo, 0, kk);
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-        dp = mfma32(a[kk & 3], vf[kk], dp);
-        if (kk < 4) a[kk & 3] = read_rows_o(sG, lo, 0, kk + 4);
-        else ga[kk - 4] = read_cols_o(sG, lo, 0, kk - 4);
-    }
+        for (int kk = 0; kk < 8; ++kk) {
 #pragma unroll
-    for (int db = 0; db < 4; ++db) qa[db] = read_cols_o(sQ, lo, 0, db);
+            for (int nb = 0; nb < KV_NB; ++nb) s[nb] = mfma32(a[kk & 3], kf[nb][kk], s[nb]);
+            a[kk & 3] = kk < 4 ? read_rows_o(sQ, lo, 0, kk + 4) : read_rows_o(sG, lo, 0, kk - 4);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int a4 = 0; a4 < 4; ++a4) {
-        const int rb = 8 * a4 + 4 * g;
-        const f32x4 l4 = *reinterpret_cast<const f32x4*>(sLD + rb);
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(sLD + 32 + rb);
+        for (int a4 = 0; a4 < 4; ++a4) {
+            const int rb = 8 * a4 + 4 * g;
+            const f32x4 l4 = *reinterpret_cast<const f32x4*>(sLD + rb);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int i = a4 * 4 + r;
-            float pr = fast_exp2(__builtin_fmaf(s[i], c2, l4[r] * -1.4426950408889634f));
-            if (MASK) {
-                const int t = r0 + rb + r;
-                int lim;  // largest key id row t sees
-                if (!GATHER) lim = t;
-                else if (UNIFORM) lim = lim_u;
-                else lim = gather_count(D, (t - D.S) / D.L) - 1;
-                if (t >= tb) lim = -1;
-                pr = kcmp <= lim ? pr : 0.0f;
+            for (int r = 0; r < 4; ++r) {
+                const int i = a4 * 4 + r;
+                const float neg_l = l4[r] * -1.4426950408889634f;
+                int lim = 0;  // largest key id row t sees
+                if (MASK) {
+                    const int t = r0 + rb + r;
+                    if (!GATHER) lim = t;
+                    else if (UNIFORM) lim = lim_u;
+                    else lim = gather_count(D, (t - D.S) / D.L) - 1;
+                    if (t >= tb) lim = -1;
+                }
+#pragma unroll
+                for (int nb = 0; nb < KV_NB; ++nb) {
+                    float pr = fast_exp2(__builtin_fmaf(s[nb][i], c2, neg_l));
+                    if (MASK) pr = kcmp[nb] <= lim ? pr : 0.0f;
+                    s[nb][i] = pr;
+                }
             }
-            s[i] = pr;
-            dp[i] = pr * (dp[i] - d4[r]);
         }
+#pragma unroll
+        for (int nb = 0; nb < KV_NB; ++nb) { pf[nb][0] = pack8(s[nb], 0); pf[nb][1] = pack8(s[nb], 8); }
     }
-    bf16x8 gb[4], qb[4];
+    __builtin_amdgcn_sched_barrier(0);
+    bf16x8 dsf[KV_NB][2];  // dS = A * (dA - D), the rounded A is reused
     {
-        const bf16x8 pf = pack8(s, 0);
-        const bf16x8 dsf = pack8(dp, 0);
+        f32x16 dp[KV_NB];
+#pragma unroll
+        for (int nb = 0; nb < KV_NB; ++nb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dp[nb][i] = 0.0f;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+#pragma unroll
+            for (int nb = 0; nb < KV_NB; ++nb) dp[nb] = mfma32(a[kk & 3], vf[nb][kk], dp[nb]);
+            a[kk & 3] = kk < 4 ? read_rows_o(sG, lo, 0, kk + 4) : read_cols_o(sG, lo, 0, kk - 4);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int a4 = 0; a4 < 4; ++a4) {
+            const f32x4 d4 = *reinterpret_cast<const f32x4*>(sLD + 32 + 8 * a4 + 4 * g);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int i = a4 * 4 + r;
+#pragma unroll
+                for (int nb = 0; nb < KV_NB; ++nb) {
+                    const float pr = float(pf[nb][i >> 3][i & 7]);
+                    dp[nb][i] = pr * (dp[nb][i] - d4[r]);
+                }
+            }
+        }
+#pragma unroll
+        for (int nb = 0; nb < KV_NB; ++nb) { dsf[nb][0] = pack8(dp[nb], 0); dsf[nb][1] = pack8(dp[nb], 8); }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // dV^T += dO^T A and dK^T += Q^T dS, 16 rows at a time
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
-            dv[db] = mfma32(ga[db], pf, dv[db]);
-            gb[db] = read_cols_o(sG, lo, 16, db);
+#pragma unroll
+            for (int nb = 0; nb < KV_NB; ++nb) dv[nb][db] = mfma32(a[db], pf[nb][hh], dv[nb][db]);
+            a[db] = read_cols_o(sQ, lo, hh * 16, db);
         }
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
-            dk[db] = mfma32(qa[db], dsf, dk[db]);
-            qb[db] = read_cols_o(sQ, lo, 16, db);
+#pragma unroll
+            for (int nb = 0; nb < KV_NB; ++nb) dk[nb][db] = mfma32(a[db], dsf[nb][hh], dk[nb][db]);
+            if (hh == 0) a[db] = read_cols_o(sG, lo, 16, db);
         }
     }
-    {
-        const bf16x8 pf = pack8(s, 8);
-        const bf16x8 dsf = pack8(dp, 8);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) dv[db] = mfma32(gb[db], pf, dv[db]);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) dk[db] = mfma32(qb[db], dsf, dk[db]);
-    }
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 constexpr int KV_STAGES = 4;
@@ -412,23 +443,25 @@ __global__ __launch_bounds__(BWD_THREADS, 1) void k_bwd_dkv(Dims D, const bf16_t
     const int sph = (nr + KV_BQ - 1) / KV_BQ;   // steps per head
     const int nsteps = sph * D.G;
 
-    // ---- this lane's key column: fragments of K and V stay in registers
-    const int kid = key0 + wave * 32 + l32;
-    const bool kvalid = kid < key_end;
-    const int kid_ld = kvalid ? kid : key_end - 1;
-    const int kpos = GATHER ? (kid_ld < D.S ? kid_ld : idx_h[kid_ld - D.S]) : kid_ld;
-    const int kcmp = kvalid ? kid : 0x7fffffff;
-    bf16x8 kf[8], vf[8];
-    {
+    // ---- this lane's key columns (one per 32-key block): fragments of K and V stay in registers
+    const int wave_key0 = key0 + wave * (32 * KV_NB);
+    const bool wave_keys_valid = wave_key0 + 32 * KV_NB - 1 < key_end;
+    int kid[KV_NB], kcmp[KV_NB];
+    bf16x8 kf[KV_NB][8], vf[KV_NB][8];
+#pragma unroll
+    for (int nb = 0; nb < KV_NB; ++nb) {
+        kid[nb] = wave_key0 + nb * 32 + l32;
+        const bool kvalid = kid[nb] < key_end;
+        const int kid_ld = kvalid ? kid[nb] : key_end - 1;
+        const int kpos = GATHER ? (kid_ld < D.S ? kid_ld : idx_h[kid_ld - D.S]) : kid_ld;
+        kcmp[nb] = kvalid ? kid[nb] : 0x7fffffff;
         const int64_t koff = b * D.ks[0] + h * D.ks[1] + int64_t(kpos) * D.ks[2];
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
-            kf[kk] = *reinterpret_cast<const bf16x8*>(K + koff + kk * 16 + g * 8);
-            vf[kk] = *reinterpret_cast<const bf16x8*>(V + koff + kk * 16 + g * 8);
+            kf[nb][kk] = *reinterpret_cast<const bf16x8*>(K + koff + kk * 16 + g * 8);
+            vf[nb][kk] = *reinterpret_cast<const bf16x8*>(V + koff + kk * 16 + g * 8);
         }
     }
-    const int wave_key0 = key0 + wave * 32;
-    const bool wave_keys_valid = wave_key0 + 31 < key_end;
     const LaneOffs lo = make_lane_offs(lane);
 
     // ---- loader: wave w fills rows 8w .. 8w+7 of the Q and dO tiles (two copies of 4 rows each) and
@@ -454,11 +487,13 @@ __global__ __launch_bounds__(BWD_THREADS, 1) void k_bwd_dkv(Dims D, const bf16_t
     };
 
     const float c2 = D.scale * 1.4426950408889634f;
-    f32x16 dk[4], dv[4];
+    f32x16 dk[KV_NB][4], dv[KV_NB][4];
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int nb = 0; nb < KV_NB; ++nb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) { dk[db][i] = 0.0f; dv[db][i] = 0.0f; }
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { dk[nb][db][i] = 0.0f; dv[nb][db][i] = 0.0f; }
 
 #define LRSA_KV_STEP(step, sQ, sG, sL, sQn, sGn, sLn)                                                   \
     {                                                                                                    \
@@ -468,12 +503,13 @@ __global__ __launch_bounds__(BWD_THREADS, 1) void k_bwd_dkv(Dims D, const bf16_t
         const int r0_ = ta + ((step) % sph) * KV_BQ;                                                     \
         int lim_u_ = 0;                                                                                  \
         if (GATHER && UNIFORM) lim_u_ = gather_count(D, (r0_ - D.S) / D.L) - 1;                          \
-        /* every (row, key) pair of the step visible for this wave? */                                   \
-        const bool full_ = wave_keys_valid && r0_ + KV_BQ <= tb &&                                       \
-                           (GATHER ? (UNIFORM && lim_u_ >= wave_key0 + 31) : (r0_ >= wave_key0 + 31));   \
-        if (full_)                                                                                       \
-            dkv_step<GATHER, UNIFORM, false>(D, sQ, sG, sL + wave * 64, kf, vf, lo, dk, dv, r0_, tb, kcmp, lim_u_, c2, lane); \
-        else if (GATHER || r0_ + KV_BQ - 1 >= wave_key0) /* WINDOW: earlier rows see none of the wave's keys */ \
+        /* WINDOW: rows before the wave's first key see none of its keys.  The flag is made opaque so    */  \
+        /* that each step body stays a basic block of its own: merged into one block (or doubled into a */  \
+        /* masked and an unmasked variant) the bodies get interleaved and the register file overflows.  */  \
+        int run_ = (GATHER || r0_ + KV_BQ - 1 >= wave_key0) ? 1 : 0;                                     \
+        run_ = __builtin_amdgcn_readfirstlane(run_); /* wave-uniform by construction */                  \
+        asm volatile("" : "+s"(run_));                                                                   \
+        if (run_)                                                                                        \
             dkv_step<GATHER, UNIFORM, true>(D, sQ, sG, sL + wave * 64, kf, vf, lo, dk, dv, r0_, tb, kcmp, lim_u_, c2, lane); \
     }
 
@@ -492,64 +528,68 @@ __global__ __launch_bounds__(BWD_THREADS, 1) void k_bwd_dkv(Dims D, const bf16_t
 #undef LRSA_KV_STEP
     wait_vmcnt<0>();   // drain the copies issued past the end before the workgroup's LDS is released
 
-    if (!kvalid) return;
     const size_t part_stride = size_t(D.B) * D.Hkv * P.gl_total * 128;   // floats per slice
     const size_t part_v = size_t(P.nsl) * part_stride;                    // dV partials follow the dK partials
-    if (GATHER) {
-        float* pk = part + size_t(slice) * part_stride + ((size_t(b) * D.Hkv + h) * P.gl_total + kid) * 128;
-        float* pv = pk + part_v;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+    for (int nb = 0; nb < KV_NB; ++nb) {
+        const int kidn = kid[nb];
+        if (kidn >= key_end) continue;
+        if (GATHER) {
+            float* pk = part + size_t(slice) * part_stride + ((size_t(b) * D.Hkv + h) * P.gl_total + kidn) * 128;
+            float* pv = pk + part_v;
 #pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                f32x4 x, y;
+            for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) { x[r] = dk[db][a * 4 + r] * D.scale; y[r] = dv[db][a * 4 + r]; }
-                *reinterpret_cast<f32x4*>(pk + db * 32 + a * 8 + g * 4) = x;
-                *reinterpret_cast<f32x4*>(pv + db * 32 + a * 8 + g * 4) = y;
-            }
-    } else {
-        // gather-list entry of this position, if it is a sink token or a survivor
-        int j = -1;
-        if (P.gtiles > 0) {
-            if (kid < D.S) j = kid;
-            else {
-                const int c = (kid - D.S) / D.L;
-                if (c < D.Ns) {
-                    const int32_t* rowp = idx_h + int64_t(c) * D.K;
-                    int lo = 0, hi = D.K - 1;
-                    while (lo <= hi) {
-                        const int mid = (lo + hi) >> 1;
-                        const int v = rowp[mid];
-                        if (v == kid) { j = D.S + c * D.K + mid; break; }
-                        if (v < kid) lo = mid + 1; else hi = mid - 1;
+                for (int a = 0; a < 4; ++a) {
+                    f32x4 x, y;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) { x[r] = dk[nb][db][a * 4 + r] * D.scale; y[r] = dv[nb][db][a * 4 + r]; }
+                    *reinterpret_cast<f32x4*>(pk + db * 32 + a * 8 + g * 4) = x;
+                    *reinterpret_cast<f32x4*>(pv + db * 32 + a * 8 + g * 4) = y;
+                }
+        } else {
+            // gather-list entry of this position, if it is a sink token or a survivor
+            int j = -1;
+            if (P.gtiles > 0) {
+                if (kidn < D.S) j = kidn;
+                else {
+                    const int c = (kidn - D.S) / D.L;
+                    if (c < D.Ns) {
+                        const int32_t* rowp = idx_h + int64_t(c) * D.K;
+                        int lo_ = 0, hi_ = D.K - 1;
+                        while (lo_ <= hi_) {
+                            const int mid = (lo_ + hi_) >> 1;
+                            const int v = rowp[mid];
+                            if (v == kidn) { j = D.S + c * D.K + mid; break; }
+                            if (v < kidn) lo_ = mid + 1; else hi_ = mid - 1;
+                        }
                     }
                 }
             }
-        }
-        int nrng = 0;
-        const float* pk = nullptr;
-        if (j >= 0) {
-            const int qf0 = first_chunk_seeing(D, (j / KV_BK) * KV_BK);
-            nrng = qf0 < D.nq ? (D.nq - qf0 + P.qch - 1) / P.qch : 0;
-            pk = part + ((size_t(b) * D.Hkv + h) * P.gl_total + j) * 128;
-        }
-        const int64_t koff = b * D.ks[0] + h * D.ks[1] + int64_t(kid) * D.ks[2];
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                f32x4 x, y;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) { x[r] = dk[db][a * 4 + r] * D.scale; y[r] = dv[db][a * 4 + r]; }
-                const int dcol = db * 32 + a * 8 + g * 4;
-                for (int sidx = 0; sidx < nrng; ++sidx) {
-                    x += *reinterpret_cast<const f32x4*>(pk + size_t(sidx) * part_stride + dcol);
-                    y += *reinterpret_cast<const f32x4*>(pk + part_v + size_t(sidx) * part_stride + dcol);
-                }
-                *reinterpret_cast<bf16x4*>(dK + koff + dcol) = __builtin_convertvector(x, bf16x4);
-                *reinterpret_cast<bf16x4*>(dV + koff + dcol) = __builtin_convertvector(y, bf16x4);
+            int nrng = 0;
+            const float* pk = nullptr;
+            if (j >= 0) {
+                const int qf0 = first_chunk_seeing(D, (j / KV_BK) * KV_BK);
+                nrng = qf0 < D.nq ? (D.nq - qf0 + P.qch - 1) / P.qch : 0;
+                pk = part + ((size_t(b) * D.Hkv + h) * P.gl_total + j) * 128;
             }
+            const int64_t koff = b * D.ks[0] + h * D.ks[1] + int64_t(kidn) * D.ks[2];
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    f32x4 x, y;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) { x[r] = dk[nb][db][a * 4 + r] * D.scale; y[r] = dv[nb][db][a * 4 + r]; }
+                    const int dcol = db * 32 + a * 8 + g * 4;
+                    for (int sidx = 0; sidx < nrng; ++sidx) {
+                        x += *reinterpret_cast<const f32x4*>(pk + size_t(sidx) * part_stride + dcol);
+                        y += *reinterpret_cast<const f32x4*>(pk + part_v + size_t(sidx) * part_stride + dcol);
+                    }
+                    *reinterpret_cast<bf16x4*>(dK + koff + dcol) = __builtin_convertvector(x, bf16x4);
+                    *reinterpret_cast<bf16x4*>(dV + koff + dcol) = __builtin_convertvector(y, bf16x4);
+                }
+        }
     }
 }
 
