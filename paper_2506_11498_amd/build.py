@@ -3,6 +3,7 @@ from __future__ import annotations
 
 import glob
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -18,14 +19,33 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+# Kernels that count their own outstanding vector-memory operations (s_waitcnt vmcnt(n) around an
+# asynchronous LDS ring) must not spill: scratch traffic would be counted by the same counter.
+NO_SCRATCH = ("k_fwd_mfma", "k_bwd_dq", "k_bwd_dkv")
+
+
+def _check_scratch(remarks: str, src: str) -> None:
+    name = None
+    for line in remarks.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+        m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m and name and "generic" not in name and any(k in name for k in NO_SCRATCH) and int(m.group(1)) != 0:
+            raise RuntimeError(f"{src}: kernel {name} spills {m.group(1)} bytes/lane to scratch; "
+                               "its vmcnt accounting requires none")
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.basename(src) + ".o")
-    cmd = [HIPCC, *FLAGS, "-c", src, "-o", obj]
+    cmd = [HIPCC, *FLAGS, "-Rpass-analysis=kernel-resource-usage", "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
+    remarks = [l for l in r.stderr.splitlines() if "remark:" in l]
     if r.returncode != 0:
-        raise RuntimeError(f"hipcc failed on {src}:\n{err}")
+        raise RuntimeError(f"hipcc failed on {src}:\n" + "\n".join(l for l in r.stderr.splitlines() if noise not in l and "remark:" not in l))
+    err = "\n".join(l for l in r.stderr.splitlines() if "warning:" in l and noise not in l)
+    _check_scratch("\n".join(remarks), src)
     if err.strip():
         sys.stderr.write(err + "\n")
     return obj

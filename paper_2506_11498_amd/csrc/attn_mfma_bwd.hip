@@ -21,9 +21,11 @@
 namespace lrsa {
 
 constexpr int BWD_THREADS = 256;
+constexpr int KV_WAVES = 8;            // waves per workgroup of the key-outer kernel (two per SIMD)
+constexpr int KV_THREADS = 64 * KV_WAVES;
 constexpr int DQ_BM = 128, DQ_BN = 64;
-constexpr int KV_NB = 2;              // 32-key blocks per wave
-constexpr int KV_BK = 128 * KV_NB;   // keys per workgroup (32*KV_NB per wave)
+constexpr int KV_NB = 1;                        // 32-key blocks per wave
+constexpr int KV_BK = 32 * KV_NB * KV_WAVES;   // keys per workgroup
 constexpr int KV_BQ = 32;   // query rows per step
 constexpr int KV_MAX_SLICES = 8;
 
@@ -273,17 +275,23 @@ __device__ __forceinline__ int first_chunk_seeing(const Dims& D, int j0) {
 
 // One step (32 query rows) of the key-outer walk for one wave.  sLD holds this wave's copy of the
 // rows' lse (floats 0..31) and D (floats 32..63).  r0 = first row of the step; rows >= tb are padding.
-// lim_u: GATHER with chunk-aligned steps: the largest gather-list entry the step's chunk sees.
-template <bool GATHER, bool UNIFORM, bool MASK>
+// lim_u: GATHER (steps never straddle a chunk): the largest gather-list entry the step's chunk sees.
+// The wave's K fragments are in registers, its V rows in LDS (sVw): K fragments and the accumulators
+// fill the register file.
+template <bool GATHER, bool MASK>
 __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ, const unsigned char* sG,
-                                         const float* sLD, const bf16x8 (&kf)[KV_NB][8], const bf16x8 (&vf)[KV_NB][8],
-                                         const LaneOffs& lo, f32x16 (&dk)[KV_NB][4], f32x16 (&dv)[KV_NB][4], int r0,
+                                         const float* sLD, const bf16x8 (&kf)[KV_NB][8], const unsigned char* sVw,
+                                         const LaneOffs& lo_in, f32x16 (&dk)[KV_NB][4], f32x16 (&dv)[KV_NB][4], int r0,
                                          int tb, const int (&kcmp)[KV_NB], int lim_u, float c2, int lane) {
     const int g = lane >> 5;
-    // every operand read from LDS feeds KV_NB MFMAs; operands are read four ahead of their use.
-    // The scheduling barriers keep the phases apart: without them the operand reads of later phases
-    // are hoisted over earlier ones and the register file (K, V fragments + accumulators) overflows.
-    bf16x8 a[4];
+    // the two offset registers are made opaque here so that the XORed per-block offsets are formed next
+    // to each read (one VALU op) instead of being kept in sixteen registers across the whole walk
+    LaneOffs lo = lo_in;
+    asm volatile("" : "+v"(lo.row), "+v"(lo.col));
+    // Operands are read two ahead of the MFMAs that consume them.  The scheduling barriers keep the
+    // phases apart: without them the operand reads of later phases are hoisted over earlier ones and
+    // the register file overflows.
+    bf16x8 a[2];
     bf16x8 pf[KV_NB][2];   // A = exp(S - lse) as bf16 operands, 16 rows each
     {
         f32x16 s[KV_NB];
@@ -291,13 +299,13 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
         for (int nb = 0; nb < KV_NB; ++nb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) s[nb][i] = 0.0f;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) a[kk] = read_rows_o(sQ, lo, 0, kk);
+        a[0] = read_rows_o(sQ, lo, 0, 0);
+        a[1] = read_rows_o(sQ, lo, 0, 1);
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
 #pragma unroll
-            for (int nb = 0; nb < KV_NB; ++nb) s[nb] = mfma32(a[kk & 3], kf[nb][kk], s[nb]);
-            a[kk & 3] = kk < 4 ? read_rows_o(sQ, lo, 0, kk + 4) : read_rows_o(sG, lo, 0, kk - 4);
+            for (int nb = 0; nb < KV_NB; ++nb) s[nb] = mfma32(a[kk & 1], kf[nb][kk], s[nb]);
+            a[kk & 1] = kk < 6 ? read_rows_o(sQ, lo, 0, kk + 2) : read_rows_o(sG, lo, 0, kk - 6);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -311,9 +319,7 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
                 int lim = 0;  // largest key id row t sees
                 if (MASK) {
                     const int t = r0 + rb + r;
-                    if (!GATHER) lim = t;
-                    else if (UNIFORM) lim = lim_u;
-                    else lim = gather_count(D, (t - D.S) / D.L) - 1;
+                    lim = GATHER ? lim_u : t;
                     if (t >= tb) lim = -1;
                 }
 #pragma unroll
@@ -329,17 +335,23 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
     }
     __builtin_amdgcn_sched_barrier(0);
     bf16x8 dsf[KV_NB][2];  // dS = A * (dA - D), the rounded A is reused
-    {
-        f32x16 dp[KV_NB];
+    // dA one 32-key block after the other
 #pragma unroll
-        for (int nb = 0; nb < KV_NB; ++nb)
+    for (int nb = 0; nb < KV_NB; ++nb) {
+        f32x16 dp;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) dp[nb][i] = 0.0f;
+        for (int i = 0; i < 16; ++i) dp[i] = 0.0f;
+        bf16x8 vb[2];
+        vb[0] = read_rows_o(sVw, lo, nb * 32, 0);
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
-#pragma unroll
-            for (int nb = 0; nb < KV_NB; ++nb) dp[nb] = mfma32(a[kk & 3], vf[nb][kk], dp[nb]);
-            a[kk & 3] = kk < 4 ? read_rows_o(sG, lo, 0, kk + 4) : read_cols_o(sG, lo, 0, kk - 4);
+            if (kk + 1 < 8) vb[(kk + 1) & 1] = read_rows_o(sVw, lo, nb * 32, kk + 1);
+            dp = mfma32(a[kk & 1], vb[kk & 1], dp);
+            // next operands: the rest of the dO rows, then (another block follows) the dO rows again
+            // or (last block) the first transposed dO operands
+            if (kk < 6) a[kk & 1] = read_rows_o(sG, lo, 0, kk + 2);
+            else if (nb + 1 < KV_NB) a[kk & 1] = read_rows_o(sG, lo, 0, kk - 6);
+            else a[kk & 1] = read_cols_o(sG, lo, 0, kk - 6);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -348,41 +360,38 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int i = a4 * 4 + r;
-#pragma unroll
-                for (int nb = 0; nb < KV_NB; ++nb) {
-                    const float pr = float(pf[nb][i >> 3][i & 7]);
-                    dp[nb][i] = pr * (dp[nb][i] - d4[r]);
-                }
+                const float pr = float(pf[nb][i >> 3][i & 7]);
+                dp[i] = pr * (dp[i] - d4[r]);
             }
         }
-#pragma unroll
-        for (int nb = 0; nb < KV_NB; ++nb) { dsf[nb][0] = pack8(dp[nb], 0); dsf[nb][1] = pack8(dp[nb], 8); }
+        dsf[nb][0] = pack8(dp, 0);
+        dsf[nb][1] = pack8(dp, 8);
+        __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_barrier(0);
-    // dV^T += dO^T A and dK^T += Q^T dS, 16 rows at a time
+    // dV^T += dO^T A and dK^T += Q^T dS, 16 rows at a time; the 16 operands in the order
+    // (dO^T, rows 0-15) blocks 0..3, (Q^T, rows 0-15) 0..3, (dO^T, rows 16-31), (Q^T, rows 16-31)
+#define LRSA_OPND(n) (((n) >> 2) & 1 ? read_cols_o(sQ, lo, ((n) >> 3) * 16, (n) & 3) : read_cols_o(sG, lo, ((n) >> 3) * 16, (n) & 3))
 #pragma unroll
-    for (int hh = 0; hh < 2; ++hh) {
+    for (int n = 0; n < 16; ++n) {
+        const int hh = n >> 3, db = n & 3;
+        if ((n >> 2) & 1) {
 #pragma unroll
-        for (int db = 0; db < 4; ++db) {
+            for (int nb = 0; nb < KV_NB; ++nb) dk[nb][db] = mfma32(a[n & 1], dsf[nb][hh], dk[nb][db]);
+        } else {
 #pragma unroll
-            for (int nb = 0; nb < KV_NB; ++nb) dv[nb][db] = mfma32(a[db], pf[nb][hh], dv[nb][db]);
-            a[db] = read_cols_o(sQ, lo, hh * 16, db);
+            for (int nb = 0; nb < KV_NB; ++nb) dv[nb][db] = mfma32(a[n & 1], pf[nb][hh], dv[nb][db]);
         }
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-#pragma unroll
-            for (int nb = 0; nb < KV_NB; ++nb) dk[nb][db] = mfma32(a[db], dsf[nb][hh], dk[nb][db]);
-            if (hh == 0) a[db] = read_cols_o(sG, lo, 16, db);
-        }
+        if (n + 2 < 16) a[n & 1] = LRSA_OPND(n + 2);
     }
+#undef LRSA_OPND
     __builtin_amdgcn_sched_barrier(0);
 }
 
 constexpr int KV_STAGES = 4;
-constexpr int KV_LOADS_PER_STEP = 5;   // asynchronous copies one wave issues per step: 2 Q, 2 dO, 1 lse|D
+constexpr int KV_LOADS_PER_STEP = 3;   // asynchronous copies one wave issues per step: 4 Q rows, 4 dO rows, lse|D
 
-template <bool GATHER, bool UNIFORM>
-__global__ __launch_bounds__(BWD_THREADS, 1) void k_bwd_dkv(Dims D, const bf16_t* __restrict__ Q,
+template <bool GATHER>
+__global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t* __restrict__ Q,
                                                              const bf16_t* __restrict__ K,
                                                              const bf16_t* __restrict__ V,
                                                              const bf16_t* __restrict__ dO,
@@ -397,7 +406,9 @@ __global__ __launch_bounds__(BWD_THREADS, 1) void k_bwd_dkv(Dims D, const bf16_t
         sQ2[KV_BQ * TILE_ROW_BYTES], sQ3[KV_BQ * TILE_ROW_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char sG0[KV_BQ * TILE_ROW_BYTES], sG1[KV_BQ * TILE_ROW_BYTES],
         sG2[KV_BQ * TILE_ROW_BYTES], sG3[KV_BQ * TILE_ROW_BYTES];
-    __shared__ __attribute__((aligned(16))) float sL0[4 * 64], sL1[4 * 64], sL2[4 * 64], sL3[4 * 64];
+    __shared__ __attribute__((aligned(16))) float sL0[KV_WAVES * 64], sL1[KV_WAVES * 64], sL2[KV_WAVES * 64],
+        sL3[KV_WAVES * 64];
+    __shared__ __attribute__((aligned(16))) unsigned char sVk[KV_BK * TILE_ROW_BYTES];   // the workgroup's V rows
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
@@ -407,6 +418,7 @@ __global__ __launch_bounds__(BWD_THREADS, 1) void k_bwd_dkv(Dims D, const bf16_t
     // ---- which keys, which query rows
     int key0, key_end;   // key ids of this workgroup: positions (WINDOW) or gather-list entries (GATHER)
     int ta, tb;          // query rows [ta, tb) of every head of the group
+    int qa = 0;          // GATHER: first query chunk of the slice
     int slice = 0;
     if (GATHER) {
         // consecutive workgroups take consecutive list tiles of ONE query slice, so the Q and dO rows
@@ -415,7 +427,7 @@ __global__ __launch_bounds__(BWD_THREADS, 1) void k_bwd_dkv(Dims D, const bf16_t
         slice = blockIdx.x / P.gtiles;
         key0 = jt * KV_BK;
         key_end = P.gl_total;
-        const int qa = first_chunk_seeing(D, key0) + slice * P.qch;
+        qa = first_chunk_seeing(D, key0) + slice * P.qch;
         if (qa >= D.nq) return;
         const int qb = min(D.nq, qa + P.qch);
         ta = D.S + qa * D.L;
@@ -439,49 +451,70 @@ __global__ __launch_bounds__(BWD_THREADS, 1) void k_bwd_dkv(Dims D, const bf16_t
         if (key0 >= key_end) return;
         ta = key0;
     }
-    const int nr = tb - ta;
-    const int sph = (nr + KV_BQ - 1) / KV_BQ;   // steps per head
+    // Steps of 32 rows.  WINDOW: consecutive rows of [ta, tb).  GATHER: chunk by chunk (the last step
+    // of a chunk may be partial), so that one step never sees two different gather-list prefixes.
+    const int spc = (D.L + KV_BQ - 1) / KV_BQ;                                   // GATHER: steps per chunk
+    const int sph = GATHER ? ((tb - ta + D.L - 1) / D.L) * spc : (tb - ta + KV_BQ - 1) / KV_BQ;   // steps per head
     const int nsteps = sph * D.G;
+    // first row, row end and chunk-visible limit of a step
+    auto step_rows = [&](int sidx, int& r0, int& rend, int& lim_u) {
+        const int w = sidx % sph;
+        if (GATHER) {
+            const int c = qa + w / spc;
+            r0 = D.S + c * D.L + (w % spc) * KV_BQ;
+            const int64_t e = int64_t(D.S) + int64_t(c + 1) * D.L;
+            rend = e < tb ? int(e) : tb;
+            lim_u = gather_count(D, c) - 1;
+        } else {
+            r0 = ta + w * KV_BQ;
+            rend = tb;
+            lim_u = 0;
+        }
+    };
 
-    // ---- this lane's key columns (one per 32-key block): fragments of K and V stay in registers
+    // ---- this lane's key columns (one per 32-key block): K fragments stay in registers, the V rows
+    // go to LDS in the swizzled tile layout (row = key within the workgroup)
     const int wave_key0 = key0 + wave * (32 * KV_NB);
-    const bool wave_keys_valid = wave_key0 + 32 * KV_NB - 1 < key_end;
-    int kid[KV_NB], kcmp[KV_NB];
-    bf16x8 kf[KV_NB][8], vf[KV_NB][8];
+    int kcmp[KV_NB];
+    bf16x8 kf[KV_NB][8];
 #pragma unroll
     for (int nb = 0; nb < KV_NB; ++nb) {
-        kid[nb] = wave_key0 + nb * 32 + l32;
-        const bool kvalid = kid[nb] < key_end;
-        const int kid_ld = kvalid ? kid[nb] : key_end - 1;
+        const int kidn = wave_key0 + nb * 32 + l32;
+        const bool kvalid = kidn < key_end;
+        const int kid_ld = kvalid ? kidn : key_end - 1;
         const int kpos = GATHER ? (kid_ld < D.S ? kid_ld : idx_h[kid_ld - D.S]) : kid_ld;
-        kcmp[nb] = kvalid ? kid[nb] : 0x7fffffff;
+        kcmp[nb] = kvalid ? kidn : 0x7fffffff;
         const int64_t koff = b * D.ks[0] + h * D.ks[1] + int64_t(kpos) * D.ks[2];
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            kf[nb][kk] = *reinterpret_cast<const bf16x8*>(K + koff + kk * 16 + g * 8);
-            vf[nb][kk] = *reinterpret_cast<const bf16x8*>(V + koff + kk * 16 + g * 8);
-        }
+        for (int kk = 0; kk < 8; ++kk) kf[nb][kk] = *reinterpret_cast<const bf16x8*>(K + koff + kk * 16 + g * 8);
+        const int vrow = wave * (32 * KV_NB) + nb * 32 + l32;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+            *reinterpret_cast<bf16x8*>(sVk + tile_off(vrow, kk * 2 + g)) =
+                *reinterpret_cast<const bf16x8*>(V + koff + kk * 16 + g * 8);
     }
+    const unsigned char* sVw = sVk + wave * (32 * KV_NB) * TILE_ROW_BYTES;
     const LaneOffs lo = make_lane_offs(lane);
 
-    // ---- loader: wave w fills rows 8w .. 8w+7 of the Q and dO tiles (two copies of 4 rows each) and
+    // ---- loader: wave w fills rows 4w .. 4w+3 of the Q and dO tiles (one copy of 4 rows each) and
     // its own lse|D block.  Steps past the end repeat the last one so that every wave always has the
     // same number of copies in flight.
     auto issue = [&](int step, unsigned char* sQ, unsigned char* sG, float* sL) {
         const int sc = step < nsteps ? step : nsteps - 1;
-        const int gi = sc / sph, r0 = ta + (sc % sph) * KV_BQ;
+        const int gi = sc / sph;
+        int r0, rend, lim_unused;
+        step_rows(sc, r0, rend, lim_unused);
         const int hq = h * D.G + gi;
         const int64_t base = b * D.qs[0] + hq * D.qs[1];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int r4 = 8 * wave + 4 * i;
+        {
+            const int r4 = 4 * wave;   // 8 waves x 4 rows = the 32 rows of the step
             const int row = async_row(r4, lane);
-            const int t = min(r0 + row, tb - 1);
+            const int t = min(r0 + row, rend - 1);
             const int64_t off = base + int64_t(t) * D.qs[2] + async_chunk(row, lane) * 8;
             async_rows4(Q + off, sQ, r4);
             async_rows4(dO + off, sG, r4);
         }
-        const int t = min(r0 + l32, tb - 1);
+        const int t = min(r0 + l32, rend - 1);
         const float* src = (g ? Dsum : lse) + (int64_t(b) * D.Hq + hq) * D.n + t;
         __builtin_amdgcn_global_load_lds((gbl_void_t*)src, (lds_void_t*)(sL + wave * 64), 4, 0, 0);
     };
@@ -500,9 +533,8 @@ __global__ __launch_bounds__(BWD_THREADS, 1) void k_bwd_dkv(Dims D, const bf16_t
         wait_vmcnt<(KV_STAGES - 2) * KV_LOADS_PER_STEP>(); /* this wave's copies for `step` landed */   \
         __syncthreads();                                     /* everybody's did; stage of step-1 free */ \
         issue((step) + KV_STAGES - 1, sQn, sGn, sLn);                                                    \
-        const int r0_ = ta + ((step) % sph) * KV_BQ;                                                     \
-        int lim_u_ = 0;                                                                                  \
-        if (GATHER && UNIFORM) lim_u_ = gather_count(D, (r0_ - D.S) / D.L) - 1;                          \
+        int r0_, rend_, lim_u_;                                                                          \
+        step_rows(step, r0_, rend_, lim_u_);                                                             \
         /* WINDOW: rows before the wave's first key see none of its keys.  The flag is made opaque so    */  \
         /* that each step body stays a basic block of its own: merged into one block (or doubled into a */  \
         /* masked and an unmasked variant) the bodies get interleaved and the register file overflows.  */  \
@@ -510,7 +542,7 @@ __global__ __launch_bounds__(BWD_THREADS, 1) void k_bwd_dkv(Dims D, const bf16_t
         run_ = __builtin_amdgcn_readfirstlane(run_); /* wave-uniform by construction */                  \
         asm volatile("" : "+s"(run_));                                                                   \
         if (run_)                                                                                        \
-            dkv_step<GATHER, UNIFORM, true>(D, sQ, sG, sL + wave * 64, kf, vf, lo, dk, dv, r0_, tb, kcmp, lim_u_, c2, lane); \
+            dkv_step<GATHER, true>(D, sQ, sG, sL + wave * 64, kf, sVw, lo, dk, dv, r0_, rend_, kcmp, lim_u_, c2, lane); \
     }
 
     issue(0, sQ0, sG0, sL0);
@@ -532,7 +564,7 @@ __global__ __launch_bounds__(BWD_THREADS, 1) void k_bwd_dkv(Dims D, const bf16_t
     const size_t part_v = size_t(P.nsl) * part_stride;                    // dV partials follow the dK partials
 #pragma unroll
     for (int nb = 0; nb < KV_NB; ++nb) {
-        const int kidn = kid[nb];
+        const int kidn = key0 + wave * (32 * KV_NB) + nb * 32 + (lane & 31);
         if (kidn >= key_end) continue;
         if (GATHER) {
             float* pk = part + size_t(slice) * part_stride + ((size_t(b) * D.Hkv + h) * P.gl_total + kidn) * 128;
@@ -611,18 +643,11 @@ hipError_t launch_attn_bwd_mfma(const Dims& D, const void* Q, const void* K, con
         LRSA_TIMED_LAUNCH("k_bwd_dq", st, k_bwd_dq, dim3(qtiles, D.Hq, D.B), dim3(BWD_THREADS), 0, st, D, q, k, v, g, lse, Dsum, idx,
                            (bf16_t*)dQ, P.sink_tiles_q, P.tpc_q);
     if (P.gtiles > 0)
-    {
-        // steps of 32 rows stay inside one query chunk when the lag is a multiple of 32
-        if (D.L % KV_BQ == 0)
-            LRSA_TIMED_LAUNCH("k_bwd_dkv_gather", st, (k_bwd_dkv<true, true>), dim3(P.gtiles * P.nsl, D.Hkv, D.B),
-                              dim3(BWD_THREADS), 0, st, D, q, k, v, g, lse, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
-        else
-            LRSA_TIMED_LAUNCH("k_bwd_dkv_gather", st, (k_bwd_dkv<true, false>), dim3(P.gtiles * P.nsl, D.Hkv, D.B),
-                              dim3(BWD_THREADS), 0, st, D, q, k, v, g, lse, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
-    }
+        LRSA_TIMED_LAUNCH("k_bwd_dkv_gather", st, k_bwd_dkv<true>, dim3(P.gtiles * P.nsl, D.Hkv, D.B), dim3(KV_THREADS), 0,
+                          st, D, q, k, v, g, lse, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
     const int ktiles = P.sink_tiles_k + D.nq * P.tpc_k;
     if (ktiles > 0)
-        LRSA_TIMED_LAUNCH("k_bwd_dkv_window", st, (k_bwd_dkv<false, true>), dim3(ktiles, D.Hkv, D.B), dim3(BWD_THREADS), 0,
+        LRSA_TIMED_LAUNCH("k_bwd_dkv_window", st, k_bwd_dkv<false>, dim3(ktiles, D.Hkv, D.B), dim3(KV_THREADS), 0,
                           st, D, q, k, v, g, lse, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
     return hipGetLastError();
 }

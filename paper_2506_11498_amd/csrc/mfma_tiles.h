@@ -59,33 +59,31 @@ __device__ __forceinline__ bf16x8 read_cols(const unsigned char* tile, int rb16,
     return u.v;
 }
 
-// Per-lane byte offsets of the two read patterns inside a tile, computed once: the swizzle only looks
-// at the low four bits of the row, so other row blocks (multiples of 16 rows) are immediates on top.
+// Per-lane byte offsets of the two read patterns inside a tile.  Because the swizzle is an XOR on
+// chunk bits that the channel-block index also occupies, the offset of channel block kk (or db, and of
+// the second transposing read) is the block-0 offset XOR a compile-time constant: two registers per
+// lane describe every read, other row blocks (multiples of 16 rows) are immediates on top.
 struct LaneOffs {
-    int row[8];      // read_rows: row l32, channel block kk
-    int col[4][2];   // read_cols: channel block db, first / second transposing read
+    int row;   // read_rows: row l32, channel block 0
+    int col;   // read_cols: channel block 0, first transposing read
 };
 __device__ __forceinline__ LaneOffs make_lane_offs(int lane) {
     LaneOffs o;
     const int l32 = lane & 31, g = lane >> 5, lam = lane & 15, m = (lane >> 4) & 1;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) o.row[kk] = tile_off(l32, kk * 2 + g);
-#pragma unroll
-    for (int db = 0; db < 4; ++db) {
-        const int ch = db * 32 + 16 * m + 4 * (lam & 3);
-#pragma unroll
-        for (int jh = 0; jh < 2; ++jh) o.col[db][jh] = tile_off(4 * g + (lam >> 2) + 8 * jh, ch >> 3) + (ch & 7) * 2;
-    }
+    o.row = tile_off(l32, g);
+    const int ch = 16 * m + 4 * (lam & 3);
+    o.col = tile_off(4 * g + (lam >> 2), ch >> 3) + (ch & 7) * 2;
     return o;
 }
-// same operands as read_rows / read_cols, from the precomputed offsets; rb is a multiple of 32, rb16 of 16
+// same operands as read_rows / read_cols; rb is a multiple of 32, rb16 of 16
 __device__ __forceinline__ bf16x8 read_rows_o(const unsigned char* tile, const LaneOffs& o, int rb, int kk) {
-    return *reinterpret_cast<const bf16x8*>(tile + o.row[kk] + rb * TILE_ROW_BYTES);
+    return *reinterpret_cast<const bf16x8*>(tile + (o.row ^ (kk << 5)) + rb * TILE_ROW_BYTES);
 }
 __device__ __forceinline__ bf16x8 read_cols_o(const unsigned char* tile, const LaneOffs& o, int rb16, int db) {
     typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(tile + o.col[db][0] + rb16 * TILE_ROW_BYTES));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(tile + o.col[db][1] + rb16 * TILE_ROW_BYTES));
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(tile + (o.col ^ (db << 6)) + rb16 * TILE_ROW_BYTES));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_ptr)(tile + (o.col ^ ((db << 6) | 32)) + (rb16 + 8) * TILE_ROW_BYTES));
     union { s16x4 h[2]; bf16x8 v; } u;
     u.h[0] = lo;
     u.h[1] = hi;
