@@ -410,7 +410,8 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
         sL3[KV_WAVES * 64];
     __shared__ __attribute__((aligned(16))) unsigned char sVk[KV_BK * TILE_ROW_BYTES];   // the workgroup's V rows
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: kept in a scalar register
     const int l32 = lane & 31, g = lane >> 5;
     const int h = blockIdx.y, b = blockIdx.z;
     const int32_t* idx_h = idx + (int64_t(b) * D.Hkv + h) * D.Ns * D.K;
