@@ -158,7 +158,7 @@ def main():
         return sum(kern_ms.get(k, 0.0) * launches.get(k, 0.0) for k in names)
     esz = 2 if w.dtype == "bf16" else 4
     score_bytes = 2 * w.B * w.Hkv * w.n * w.d * esz + 4 * w.B * w.Hkv * Ns * w.L
-    ms_score = stage(["k_minmaxT", "k_sigmaT", "k_softmax"])
+    ms_score = stage(["k_score_fused", "k_minmaxT", "k_sigmaT", "k_softmax"])
     ms_select = stage(["k_select"])
     ms_fwd = stage(["k_fwd_mfma", "k_fwd_genericT"])
     ms_bwd = stage(["k_bwd_rowdot", "k_bwd_dq", "k_bwd_dkv_gather", "k_bwd_dkv_window", "k_bwd_dq_genericT", "k_bwd_dkv_genericT"])

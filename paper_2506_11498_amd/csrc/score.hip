@@ -18,10 +18,6 @@ __host__ __device__ inline int score_rows_per_wg(int L) { return L < 256 ? L : 2
 __host__ __device__ inline int score_splits(int L) { int r = score_rows_per_wg(L); return (L + r - 1) / r; }
 
 // workspace layout: mm[unit][split][2][d] floats, then sigma[unit][L] floats; unit = ((b*Hkv+h)*2+z)*Ns+p
-struct ScoreWs {
-    float* mm;
-    float* sigma;
-};
 static inline size_t mm_floats(const Dims& D) { return size_t(D.B) * D.Hkv * 2 * D.Ns * score_splits(D.L) * 2 * D.d; }
 static inline size_t sigma_floats(const Dims& D) { return size_t(D.B) * D.Hkv * 2 * D.Ns * D.L; }
 
@@ -170,8 +166,158 @@ __global__ __launch_bounds__(SCORE_THREADS) void k_softmax(Dims D, const float* 
         out[r] = expf(sk[r] - mk) / zk + expf(sv[r] - mv) / zv;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Fused variant: one workgroup of 1024 threads per (batch, KV head, chunk p) does all of Eq. 4-8:
+//   phase 1  per-channel min / max of K and of V over chunk p+1 (registers -> wave shuffles -> LDS)
+//   phase 2  rows of chunk p normalised (Eq. 6), Std over channels -> sigma_K, sigma_V in LDS
+//   phase 3  softmax over the chunk's tokens for K and V, summed, written out
+// Chunk p+1 is read here as the reference and, at about the same time, by workgroup p+1 as its scored
+// chunk, so the second read is served by L2 / the memory-side cache.  The division of Eq. 6 is done as
+// a multiplication by the correctly rounded reciprocal plus one fused residual correction
+// (q + (a - b*q) * rcp), which reproduces the IEEE quotient.
+constexpr int FUSED_THREADS = 1024;
+constexpr int FUSED_MAX_L = 4096;
+
+template <typename T>
+__global__ __launch_bounds__(FUSED_THREADS) void k_score_fused(Dims D, const T* __restrict__ Kp,
+                                                               const T* __restrict__ Vp,
+                                                               float* __restrict__ score) {
+    constexpr int VEC = Elem<T>::VEC;
+    constexpr int NW = FUSED_THREADS / 64;
+    const int lpr = D.d / VEC;                // lanes per row
+    const int rpp = FUSED_THREADS / lpr;      // rows per pass
+    const int p = blockIdx.x, bh = blockIdx.y;
+    const int b = bh / D.Hkv, h = bh % D.Hkv;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = tid % lpr, rg = tid / lpr;
+    const int64_t hoff = b * D.ks[0] + h * D.ks[1];
+    const int64_t ref0 = int64_t(D.S) + int64_t(p + 1) * D.L;   // first row of the reference chunk
+    const int64_t cur0 = int64_t(D.S) + int64_t(p) * D.L;       // first row of the scored chunk
+
+    __shared__ float red[4][NW][128];     // per-wave partial min_K, max_K, min_V, max_V
+    __shared__ float s_mn[2][128], s_inv[2][128], s_den[2][128];
+    __shared__ float sig[2][FUSED_MAX_L];
+    __shared__ float sm[NW];
+
+    // ---- phase 1
+    {
+        float mn[2][VEC], mx[2][VEC];
+#pragma unroll
+        for (int z = 0; z < 2; ++z)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) { mn[z][i] = INFINITY; mx[z][i] = -INFINITY; }
+        for (int r = rg; r < D.L; r += 2 * rpp) {
+            // two rows of K and of V in flight
+            const int r2 = r + rpp < D.L ? r + rpp : r;
+            float k0[VEC], k1[VEC], v0[VEC], v1[VEC];
+            Elem<T>::load(Kp + hoff + (ref0 + r) * D.ks[2] + sub * VEC, k0);
+            Elem<T>::load(Vp + hoff + (ref0 + r) * D.ks[2] + sub * VEC, v0);
+            Elem<T>::load(Kp + hoff + (ref0 + r2) * D.ks[2] + sub * VEC, k1);
+            Elem<T>::load(Vp + hoff + (ref0 + r2) * D.ks[2] + sub * VEC, v1);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                mn[0][i] = fminf(mn[0][i], fminf(k0[i], k1[i])); mx[0][i] = fmaxf(mx[0][i], fmaxf(k0[i], k1[i]));
+                mn[1][i] = fminf(mn[1][i], fminf(v0[i], v1[i])); mx[1][i] = fmaxf(mx[1][i], fmaxf(v0[i], v1[i]));
+            }
+        }
+        // lanes of one wave that hold the same channels (different rows): shuffle over the row groups
+        for (int o = lpr; o < 64; o <<= 1)
+#pragma unroll
+            for (int z = 0; z < 2; ++z)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    mn[z][i] = fminf(mn[z][i], __shfl_xor(mn[z][i], o, 64));
+                    mx[z][i] = fmaxf(mx[z][i], __shfl_xor(mx[z][i], o, 64));
+                }
+        if (lane < lpr) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                red[0][wave][lane * VEC + i] = mn[0][i]; red[1][wave][lane * VEC + i] = mx[0][i];
+                red[2][wave][lane * VEC + i] = mn[1][i]; red[3][wave][lane * VEC + i] = mx[1][i];
+            }
+        }
+        __syncthreads();
+        if (tid < 2 * D.d) {
+            const int z = tid / D.d, c = tid % D.d;
+            float a = INFINITY, m = -INFINITY;
+            for (int w = 0; w < NW; ++w) { a = fminf(a, red[2 * z][w][c]); m = fmaxf(m, red[2 * z + 1][w][c]); }
+            float den = m - a;
+            den = den == 0.0f ? 1.0f : den;
+            s_mn[z][c] = a;
+            s_den[z][c] = den;
+            s_inv[z][c] = 1.0f / den;
+        }
+        __syncthreads();
+    }
+    // ---- phase 2
+    {
+        for (int z = 0; z < 2; ++z) {
+            const T* Z = (z ? Vp : Kp) + hoff;
+            float mn[VEC], den[VEC], inv[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) { mn[i] = s_mn[z][sub * VEC + i]; den[i] = s_den[z][sub * VEC + i]; inv[i] = s_inv[z][sub * VEC + i]; }
+            for (int r = rg; r < D.L; r += 2 * rpp) {
+                const bool has2 = r + rpp < D.L;
+                const int r2 = has2 ? r + rpp : r;
+                float x0[VEC], x1[VEC];
+                Elem<T>::load(Z + (cur0 + r) * D.ks[2] + sub * VEC, x0);
+                Elem<T>::load(Z + (cur0 + r2) * D.ks[2] + sub * VEC, x1);
+                float s0 = 0.0f, s1 = 0.0f;
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    const float a0 = x0[i] - mn[i], a1 = x1[i] - mn[i];
+                    float q0 = a0 * inv[i], q1 = a1 * inv[i];
+                    q0 = __builtin_fmaf(__builtin_fmaf(-den[i], q0, a0), inv[i], q0);
+                    q1 = __builtin_fmaf(__builtin_fmaf(-den[i], q1, a1), inv[i], q1);
+                    x0[i] = q0; x1[i] = q1;
+                    s0 += q0; s1 += q1;
+                }
+                for (int o = lpr >> 1; o > 0; o >>= 1) { s0 += __shfl_xor(s0, o, 64); s1 += __shfl_xor(s1, o, 64); }
+                const float m0 = s0 / float(D.d), m1 = s1 / float(D.d);
+                float v0 = 0.0f, v1 = 0.0f;
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    const float d0 = x0[i] - m0, d1 = x1[i] - m1;
+                    v0 += d0 * d0; v1 += d1 * d1;
+                }
+                for (int o = lpr >> 1; o > 0; o >>= 1) { v0 += __shfl_xor(v0, o, 64); v1 += __shfl_xor(v1, o, 64); }
+                if (sub == 0) {
+                    sig[z][r] = sqrtf(v0 / float(D.d - D.ddof));
+                    if (has2) sig[z][r2] = sqrtf(v1 / float(D.d - D.ddof));
+                }
+            }
+        }
+        __syncthreads();
+    }
+    // ---- phase 3
+    auto block_red = [&](float v, bool is_max) {
+        v = is_max ? wave_max(v) : wave_sum(v);
+        __syncthreads();
+        if (lane == 0) sm[wave] = v;
+        __syncthreads();
+        float r = sm[0];
+        for (int i = 1; i < NW; ++i) r = is_max ? fmaxf(r, sm[i]) : r + sm[i];
+        return r;
+    };
+    float mk = -INFINITY, mv = -INFINITY;
+    for (int r = tid; r < D.L; r += FUSED_THREADS) { mk = fmaxf(mk, sig[0][r]); mv = fmaxf(mv, sig[1][r]); }
+    mk = block_red(mk, true);
+    mv = block_red(mv, true);
+    float zk = 0.0f, zv = 0.0f;
+    for (int r = tid; r < D.L; r += FUSED_THREADS) { zk += expf(sig[0][r] - mk); zv += expf(sig[1][r] - mv); }
+    zk = block_red(zk, false);
+    zv = block_red(zv, false);
+    float* out = score + (int64_t(bh) * D.Ns + p) * D.L;
+    for (int r = tid; r < D.L; r += FUSED_THREADS) out[r] = expf(sig[0][r] - mk) / zk + expf(sig[1][r] - mv) / zv;
+}
+
 template <typename T>
 static hipError_t run_score(const Dims& D, const void* K, const void* V, float* score, void* ws, hipStream_t st) {
+    if (D.L <= FUSED_MAX_L) {
+        LRSA_TIMED_LAUNCH("k_score_fused", st, k_score_fused<T>, dim3(D.Ns, D.B * D.Hkv), dim3(FUSED_THREADS), 0, st, D,
+                          (const T*)K, (const T*)V, score);
+        return hipGetLastError();
+    }
     float* mm = reinterpret_cast<float*>(ws);
     float* sigma = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + align256(mm_floats(D) * 4));
     const dim3 grid(score_splits(D.L), D.Ns, D.B * D.Hkv * 2);
