@@ -13,7 +13,8 @@ from typing import Optional, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblrsa.so")
+# LRSA_LIB may point at another build of the same library (kernel experiments)
+LIB_PATH = os.environ.get("LRSA_LIB", os.path.join(_HERE, "liblrsa.so"))
 
 LRSA_F32, LRSA_BF16 = 0, 1
 IMPL_AUTO, IMPL_GENERIC = 0, 1

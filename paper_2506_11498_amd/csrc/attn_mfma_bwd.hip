@@ -3,7 +3,7 @@
 // D = rowsum(dO * O), dS = A * (dA - D), dQ = scale dS K, dK = scale dS^T Q.
 //
 // Deterministic, no atomics.  Four launches on one stream:
-//   k_bwd_rowdot   D[b,hq,t] = dO[t] . O[t]
+//   k_bwd_rowdot   D[b,hq,t] = dO[t] . O[t], and lse in log2 units
 //   k_bwd_dq       query-outer: a workgroup owns 128 queries and walks their key stream exactly
 //                  like the forward (gather list, then the local window), recomputing A
 //   k_bwd_dkv      key-outer, mode GATHER: a workgroup owns 128 consecutive entries of one KV
@@ -27,7 +27,7 @@ constexpr int DQ_BM = 128, DQ_BN = 64;
 constexpr int KV_NB = 1;                        // 32-key blocks per wave
 constexpr int KV_BK = 32 * KV_NB * KV_WAVES;   // keys per workgroup
 constexpr int KV_BQ = 32;   // query rows per step
-constexpr int KV_MAX_SLICES = 8;
+constexpr int KV_MAX_SLICES = 16;
 
 // ------------------------------------------------------------------------------------ host-side plan
 struct BwdPlan {
@@ -35,7 +35,7 @@ struct BwdPlan {
     int sink_tiles_k, tpc_k;    // dK/dV window mode: key tiles of 128
     int gl_total, gtiles;       // gather list length per KV head, its tiles of 128
     int qch, nsl;               // query chunks per slice, slices per gather tile (<= KV_MAX_SLICES)
-    size_t off_part, bytes;     // workspace: D first, then the fp32 partials
+    size_t off_lse2, off_part, bytes;   // workspace: D, lse in log2 units, then the fp32 partials
 };
 
 static BwdPlan make_plan(const Dims& D) {
@@ -47,15 +47,16 @@ static BwdPlan make_plan(const Dims& D) {
     P.tpc_k = (D.L + KV_BK - 1) / KV_BK;
     P.gl_total = D.nq > 0 ? D.S + D.K * D.Ns : 0;
     P.gtiles = (P.gl_total + KV_BK - 1) / KV_BK;
-    // aim at ~512 steps of 32 rows per workgroup, but never more than KV_MAX_SLICES slices
-    int64_t qch = (512 * int64_t(KV_BQ)) / (int64_t(D.L) * D.G);
+    // aim at ~256 steps of 32 rows per workgroup, but never more than KV_MAX_SLICES slices
+    int64_t qch = (256 * int64_t(KV_BQ)) / (int64_t(D.L) * D.G);
     if (qch < 1) qch = 1;
     const int min_qch = (D.nq + KV_MAX_SLICES - 1) / KV_MAX_SLICES;
     if (qch < min_qch) qch = min_qch;
     if (qch < 1) qch = 1;
     P.qch = int(qch);
     P.nsl = D.nq > 0 ? (D.nq + P.qch - 1) / P.qch : 0;
-    P.off_part = align256(size_t(D.B) * D.Hq * D.n * 4);
+    P.off_lse2 = align256(size_t(D.B) * D.Hq * D.n * 4);
+    P.off_part = 2 * P.off_lse2;
     const size_t part = size_t(2) * P.nsl * D.B * D.Hkv * P.gl_total * 128 * 4;
     P.bytes = P.off_part + align256(part);
     return P;
@@ -66,7 +67,8 @@ size_t attn_bwd_mfma_ws_bytes(const Dims& D) { return make_plan(D).bytes; }
 // ------------------------------------------------------------------------------------ D = rowsum(dO * O)
 __global__ __launch_bounds__(BWD_THREADS) void k_bwd_rowdot(Dims D, const bf16_t* __restrict__ O,
                                                              const bf16_t* __restrict__ dO,
-                                                             float* __restrict__ Dsum) {
+                                                             const float* __restrict__ lse,
+                                                             float* __restrict__ Dsum, float* __restrict__ lse2) {
     // 16 lanes per row, 16 rows per workgroup
     const int sub = threadIdx.x & 15;
     const int64_t row = int64_t(blockIdx.x) * 16 + (threadIdx.x >> 4);
@@ -84,7 +86,10 @@ __global__ __launch_bounds__(BWD_THREADS) void k_bwd_rowdot(Dims D, const bf16_t
     }
 #pragma unroll
     for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-    if (row < nrows && sub == 0) Dsum[row] = acc;
+    if (row < nrows && sub == 0) {
+        Dsum[row] = acc;
+        lse2[row] = lse[row] * 1.4426950408889634f;   // the main kernels work in log2 units
+    }
 }
 
 // ------------------------------------------------------------------------------------ dQ
@@ -190,7 +195,7 @@ __global__ __launch_bounds__(BWD_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t*
         gf[kk] = *reinterpret_cast<const bf16x8*>(dO + qoff + kk * 16 + g * 8);
     }
     const int64_t rowid = (int64_t(b) * D.Hq + hq) * D.n + tq_ld;
-    const float lse2 = lse[rowid] * 1.4426950408889634f;
+    const float lse2 = lse[rowid];   // already in log2 units
     const float Dq = Dsum[rowid];
     const int lim = ng + tq - cs;
     const int wave_lim_max = ng + min(t0 + wave * 32 + 31, t_last) - cs;
@@ -278,19 +283,17 @@ __device__ __forceinline__ int first_chunk_seeing(const Dims& D, int j0) {
 // lim_u: GATHER (steps never straddle a chunk): the largest gather-list entry the step's chunk sees.
 // The wave's K fragments are in registers, its V rows in LDS (sVw): K fragments and the accumulators
 // fill the register file.
-template <bool GATHER, bool MASK>
+template <bool GATHER>
 __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ, const unsigned char* sG,
                                          const float* sLD, const bf16x8 (&kf)[KV_NB][8], const unsigned char* sVw,
                                          const LaneOffs& lo_in, f32x16 (&dk)[KV_NB][4], f32x16 (&dv)[KV_NB][4], int r0,
-                                         int tb, const int (&kcmp)[KV_NB], int lim_u, float c2, int lane) {
+                                         int tb, const int (&kcmp)[KV_NB], int lim_u, bool need_mask, float c2, int lane) {
     const int g = lane >> 5;
     // the two offset registers are made opaque here so that the XORed per-block offsets are formed next
     // to each read (one VALU op) instead of being kept in sixteen registers across the whole walk
     LaneOffs lo = lo_in;
     asm volatile("" : "+v"(lo.row), "+v"(lo.col));
-    // Operands are read two ahead of the MFMAs that consume them.  The scheduling barriers keep the
-    // phases apart: without them the operand reads of later phases are hoisted over earlier ones and
-    // the register file overflows.
+    // Operands are read two ahead of the MFMAs that consume them.
     bf16x8 a[2];
     bf16x8 pf[KV_NB][2];   // A = exp(S - lse) as bf16 operands, 16 rows each
     {
@@ -307,33 +310,41 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
             for (int nb = 0; nb < KV_NB; ++nb) s[nb] = mfma32(a[kk & 1], kf[nb][kk], s[nb]);
             a[kk & 1] = kk < 6 ? read_rows_o(sQ, lo, 0, kk + 2) : read_rows_o(sG, lo, 0, kk - 6);
         }
-        __builtin_amdgcn_sched_barrier(0);
+        // A = exp2(S*c2 - lse2); sLD holds lse already in log2 units.  Only steps that touch the diagonal,
+        // a partly visible gather prefix, padding rows or padding keys pay for the mask (wave-uniform flag).
+        if (!need_mask) {
 #pragma unroll
-        for (int a4 = 0; a4 < 4; ++a4) {
-            const int rb = 8 * a4 + 4 * g;
-            const f32x4 l4 = *reinterpret_cast<const f32x4*>(sLD + rb);
+            for (int a4 = 0; a4 < 4; ++a4) {
+                const f32x4 l4 = *reinterpret_cast<const f32x4*>(sLD + 8 * a4 + 4 * g);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int i = a4 * 4 + r;
-                const float neg_l = l4[r] * -1.4426950408889634f;
-                int lim = 0;  // largest key id row t sees
-                if (MASK) {
-                    const int t = r0 + rb + r;
-                    lim = GATHER ? lim_u : t;
-                    if (t >= tb) lim = -1;
-                }
+                for (int r = 0; r < 4; ++r)
 #pragma unroll
-                for (int nb = 0; nb < KV_NB; ++nb) {
-                    float pr = fast_exp2(__builtin_fmaf(s[nb][i], c2, neg_l));
-                    if (MASK) pr = kcmp[nb] <= lim ? pr : 0.0f;
-                    s[nb][i] = pr;
-                }
+                    for (int nb = 0; nb < KV_NB; ++nb)
+                        s[nb][a4 * 4 + r] = fast_exp2(__builtin_fmaf(s[nb][a4 * 4 + r], c2, -l4[r]));
+            }
+        } else {
+            // row rho = 8*a4 + 4g + r of the step is visible to key block nb iff lo[nb] <= 8*a4 + r < hi
+            const int hi = (tb - r0) - 4 * g;
+            int lo[KV_NB];
+#pragma unroll
+            for (int nb = 0; nb < KV_NB; ++nb)
+                lo[nb] = GATHER ? (kcmp[nb] <= lim_u ? -64 : 64) : (kcmp[nb] == 0x7fffffff ? 64 : kcmp[nb] - r0 - 4 * g);
+#pragma unroll
+            for (int a4 = 0; a4 < 4; ++a4) {
+                const f32x4 l4 = *reinterpret_cast<const f32x4*>(sLD + 8 * a4 + 4 * g);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int nb = 0; nb < KV_NB; ++nb) {
+                        const int c = 8 * a4 + r;
+                        const float pr = fast_exp2(__builtin_fmaf(s[nb][a4 * 4 + r], c2, -l4[r]));
+                        s[nb][a4 * 4 + r] = (c >= lo[nb] && c < hi) ? pr : 0.0f;
+                    }
             }
         }
 #pragma unroll
         for (int nb = 0; nb < KV_NB; ++nb) { pf[nb][0] = pack8(s[nb], 0); pf[nb][1] = pack8(s[nb], 8); }
     }
-    __builtin_amdgcn_sched_barrier(0);
     bf16x8 dsf[KV_NB][2];  // dS = A * (dA - D), the rounded A is reused
     // dA one 32-key block after the other
 #pragma unroll
@@ -353,7 +364,6 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
             else if (nb + 1 < KV_NB) a[kk & 1] = read_rows_o(sG, lo, 0, kk - 6);
             else a[kk & 1] = read_cols_o(sG, lo, 0, kk - 6);
         }
-        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int a4 = 0; a4 < 4; ++a4) {
             const f32x4 d4 = *reinterpret_cast<const f32x4*>(sLD + 32 + 8 * a4 + 4 * g);
@@ -366,7 +376,6 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
         }
         dsf[nb][0] = pack8(dp, 0);
         dsf[nb][1] = pack8(dp, 8);
-        __builtin_amdgcn_sched_barrier(0);
     }
     // dV^T += dO^T A and dK^T += Q^T dS, 16 rows at a time; the 16 operands in the order
     // (dO^T, rows 0-15) blocks 0..3, (Q^T, rows 0-15) 0..3, (dO^T, rows 16-31), (Q^T, rows 16-31)
@@ -384,9 +393,14 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
         if (n + 2 < 16) a[n & 1] = LRSA_OPND(n + 2);
     }
 #undef LRSA_OPND
-    __builtin_amdgcn_sched_barrier(0);
 }
 
+#ifndef LRSA_DBG_NOCOMPUTE
+#define LRSA_DBG_NOCOMPUTE 0
+#endif
+#ifndef LRSA_DBG_NOLOAD
+#define LRSA_DBG_NOLOAD 0
+#endif
 constexpr int KV_STAGES = 4;
 constexpr int KV_LOADS_PER_STEP = 3;   // asynchronous copies one wave issues per step: 4 Q rows, 4 dO rows, lse|D
 
@@ -476,6 +490,7 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
     // ---- this lane's key columns (one per 32-key block): K fragments stay in registers, the V rows
     // go to LDS in the swizzled tile layout (row = key within the workgroup)
     const int wave_key0 = key0 + wave * (32 * KV_NB);
+    const bool wave_keys_valid = wave_key0 + 32 * KV_NB - 1 < key_end;
     int kcmp[KV_NB];
     bf16x8 kf[KV_NB][8];
 #pragma unroll
@@ -501,6 +516,7 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
     // its own lse|D block.  Steps past the end repeat the last one so that every wave always has the
     // same number of copies in flight.
     auto issue = [&](int step, unsigned char* sQ, unsigned char* sG, float* sL) {
+        if (LRSA_DBG_NOLOAD) return;
         const int sc = step < nsteps ? step : nsteps - 1;
         const int gi = sc / sph;
         int r0, rend, lim_unused;
@@ -542,8 +558,11 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
         int run_ = (GATHER || r0_ + KV_BQ - 1 >= wave_key0) ? 1 : 0;                                     \
         run_ = __builtin_amdgcn_readfirstlane(run_); /* wave-uniform by construction */                  \
         asm volatile("" : "+s"(run_));                                                                   \
-        if (run_)                                                                                        \
-            dkv_step<GATHER, true>(D, sQ, sG, sL + wave * 64, kf, sVw, lo, dk, dv, r0_, rend_, kcmp, lim_u_, c2, lane); \
+        /* every (row, key) pair of the step visible for this wave? */                                   \
+        const bool full_ = wave_keys_valid && r0_ + KV_BQ <= rend_ &&                                    \
+                           (GATHER ? lim_u_ >= wave_key0 + 32 * KV_NB - 1 : r0_ >= wave_key0 + 32 * KV_NB - 1); \
+        if (run_ && !LRSA_DBG_NOCOMPUTE)                                                                 \
+            dkv_step<GATHER>(D, sQ, sG, sL + wave * 64, kf, sVw, lo, dk, dv, r0_, rend_, kcmp, lim_u_, !full_, c2, lane); \
     }
 
     issue(0, sQ0, sG0, sL0);
@@ -632,24 +651,26 @@ hipError_t launch_attn_bwd_mfma(const Dims& D, const void* Q, const void* K, con
                                 void* dV, void* ws, hipStream_t st) {
     const BwdPlan P = make_plan(D);
     float* Dsum = reinterpret_cast<float*>(ws);
+    float* lse2 = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + P.off_lse2);
     float* part = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + P.off_part);
     const bf16_t *q = (const bf16_t*)Q, *k = (const bf16_t*)K, *v = (const bf16_t*)V, *o = (const bf16_t*)O,
                  *g = (const bf16_t*)dO;
 
     const int64_t nrows = int64_t(D.B) * D.Hq * D.n;
-    LRSA_TIMED_LAUNCH("k_bwd_rowdot", st, k_bwd_rowdot, dim3((unsigned)((nrows + 15) / 16)), dim3(BWD_THREADS), 0, st, D, o, g, Dsum);
+    LRSA_TIMED_LAUNCH("k_bwd_rowdot", st, k_bwd_rowdot, dim3((unsigned)((nrows + 15) / 16)), dim3(BWD_THREADS), 0, st, D, o, g, lse,
+                      Dsum, lse2);
 
     const int qtiles = P.sink_tiles_q + D.nq * P.tpc_q;
     if (qtiles > 0)
-        LRSA_TIMED_LAUNCH("k_bwd_dq", st, k_bwd_dq, dim3(qtiles, D.Hq, D.B), dim3(BWD_THREADS), 0, st, D, q, k, v, g, lse, Dsum, idx,
+        LRSA_TIMED_LAUNCH("k_bwd_dq", st, k_bwd_dq, dim3(qtiles, D.Hq, D.B), dim3(BWD_THREADS), 0, st, D, q, k, v, g, lse2, Dsum, idx,
                            (bf16_t*)dQ, P.sink_tiles_q, P.tpc_q);
     if (P.gtiles > 0)
         LRSA_TIMED_LAUNCH("k_bwd_dkv_gather", st, k_bwd_dkv<true>, dim3(P.gtiles * P.nsl, D.Hkv, D.B), dim3(KV_THREADS), 0,
-                          st, D, q, k, v, g, lse, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
+                          st, D, q, k, v, g, lse2, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
     const int ktiles = P.sink_tiles_k + D.nq * P.tpc_k;
     if (ktiles > 0)
         LRSA_TIMED_LAUNCH("k_bwd_dkv_window", st, k_bwd_dkv<false>, dim3(ktiles, D.Hkv, D.B), dim3(KV_THREADS), 0,
-                          st, D, q, k, v, g, lse, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
+                          st, D, q, k, v, g, lse2, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
     return hipGetLastError();
 }
 
