@@ -26,7 +26,9 @@ constexpr int KV_THREADS = 64 * KV_WAVES;
 constexpr int DQ_BM = 128, DQ_BN = 64;
 constexpr int KV_NB = 1;                        // 32-key blocks per wave
 constexpr int KV_BK = 32 * KV_NB * KV_WAVES;   // keys per workgroup
-constexpr int KV_BQ = 32;   // query rows per step
+constexpr int KV_BQ = 32;   // query rows per MFMA sub-step
+constexpr int KV_SUB = 2;   // sub-steps per pipeline step (one LDS stage, one barrier)
+constexpr int KV_ROWS = KV_BQ * KV_SUB;   // query rows per step
 constexpr int KV_MAX_SLICES = 16;
 
 // ------------------------------------------------------------------------------------ host-side plan
@@ -47,8 +49,8 @@ static BwdPlan make_plan(const Dims& D) {
     P.tpc_k = (D.L + KV_BK - 1) / KV_BK;
     P.gl_total = D.nq > 0 ? D.S + D.K * D.Ns : 0;
     P.gtiles = (P.gl_total + KV_BK - 1) / KV_BK;
-    // aim at ~256 steps of 32 rows per workgroup, but never more than KV_MAX_SLICES slices
-    int64_t qch = (256 * int64_t(KV_BQ)) / (int64_t(D.L) * D.G);
+    // aim at ~8192 query rows (x G heads) per workgroup, but never more than KV_MAX_SLICES slices
+    int64_t qch = (256 * 32) / (int64_t(D.L) * D.G);
     if (qch < 1) qch = 1;
     const int min_qch = (D.nq + KV_MAX_SLICES - 1) / KV_MAX_SLICES;
     if (qch < min_qch) qch = min_qch;
@@ -278,8 +280,9 @@ __device__ __forceinline__ int first_chunk_seeing(const Dims& D, int j0) {
     return j0 < D.S ? 0 : (j0 - D.S) / D.K + D.lp + 1;
 }
 
-// One step (32 query rows) of the key-outer walk for one wave.  sLD holds this wave's copy of the
-// rows' lse (floats 0..31) and D (floats 32..63).  r0 = first row of the step; rows >= tb are padding.
+// One sub-step (32 query rows: rows rowbase .. rowbase+31 of the stage tiles) of the key-outer walk for
+// one wave.  sLD holds this wave's copy of the stage rows' lse in log2 units (floats 0..KV_ROWS-1) and D
+// (the next KV_ROWS floats).  r0 = first row of the sub-step; rows >= tb are padding.
 // lim_u: GATHER (steps never straddle a chunk): the largest gather-list entry the step's chunk sees.
 // The wave's K fragments are in registers, its V rows in LDS (sVw): K fragments and the accumulators
 // fill the register file.
@@ -287,7 +290,8 @@ template <bool GATHER>
 __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ, const unsigned char* sG,
                                          const float* sLD, const bf16x8 (&kf)[KV_NB][8], const unsigned char* sVw,
                                          const LaneOffs& lo_in, f32x16 (&dk)[KV_NB][4], f32x16 (&dv)[KV_NB][4], int r0,
-                                         int tb, const int (&kcmp)[KV_NB], int lim_u, bool need_mask, float c2, int lane) {
+                                         int tb, const int (&kcmp)[KV_NB], int lim_u, bool need_mask, float c2, int lane,
+                                         int rowbase) {
     const int g = lane >> 5;
     // the two offset registers are made opaque here so that the XORed per-block offsets are formed next
     // to each read (one VALU op) instead of being kept in sixteen registers across the whole walk
@@ -302,20 +306,20 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
         for (int nb = 0; nb < KV_NB; ++nb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) s[nb][i] = 0.0f;
-        a[0] = read_rows_o(sQ, lo, 0, 0);
-        a[1] = read_rows_o(sQ, lo, 0, 1);
+        a[0] = read_rows_o(sQ, lo, rowbase, 0);
+        a[1] = read_rows_o(sQ, lo, rowbase, 1);
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
 #pragma unroll
             for (int nb = 0; nb < KV_NB; ++nb) s[nb] = mfma32(a[kk & 1], kf[nb][kk], s[nb]);
-            a[kk & 1] = kk < 6 ? read_rows_o(sQ, lo, 0, kk + 2) : read_rows_o(sG, lo, 0, kk - 6);
+            a[kk & 1] = kk < 6 ? read_rows_o(sQ, lo, rowbase, kk + 2) : read_rows_o(sG, lo, rowbase, kk - 6);
         }
         // A = exp2(S*c2 - lse2); sLD holds lse already in log2 units.  Only steps that touch the diagonal,
         // a partly visible gather prefix, padding rows or padding keys pay for the mask (wave-uniform flag).
         if (!need_mask) {
 #pragma unroll
             for (int a4 = 0; a4 < 4; ++a4) {
-                const f32x4 l4 = *reinterpret_cast<const f32x4*>(sLD + 8 * a4 + 4 * g);
+                const f32x4 l4 = *reinterpret_cast<const f32x4*>(sLD + rowbase + 8 * a4 + 4 * g);
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -331,7 +335,7 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
                 lo[nb] = GATHER ? (kcmp[nb] <= lim_u ? -64 : 64) : (kcmp[nb] == 0x7fffffff ? 64 : kcmp[nb] - r0 - 4 * g);
 #pragma unroll
             for (int a4 = 0; a4 < 4; ++a4) {
-                const f32x4 l4 = *reinterpret_cast<const f32x4*>(sLD + 8 * a4 + 4 * g);
+                const f32x4 l4 = *reinterpret_cast<const f32x4*>(sLD + rowbase + 8 * a4 + 4 * g);
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -360,13 +364,13 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
             dp = mfma32(a[kk & 1], vb[kk & 1], dp);
             // next operands: the rest of the dO rows, then (another block follows) the dO rows again
             // or (last block) the first transposed dO operands
-            if (kk < 6) a[kk & 1] = read_rows_o(sG, lo, 0, kk + 2);
-            else if (nb + 1 < KV_NB) a[kk & 1] = read_rows_o(sG, lo, 0, kk - 6);
-            else a[kk & 1] = read_cols_o(sG, lo, 0, kk - 6);
+            if (kk < 6) a[kk & 1] = read_rows_o(sG, lo, rowbase, kk + 2);
+            else if (nb + 1 < KV_NB) a[kk & 1] = read_rows_o(sG, lo, rowbase, kk - 6);
+            else a[kk & 1] = read_cols_o(sG, lo, rowbase, kk - 6);
         }
 #pragma unroll
         for (int a4 = 0; a4 < 4; ++a4) {
-            const f32x4 d4 = *reinterpret_cast<const f32x4*>(sLD + 32 + 8 * a4 + 4 * g);
+            const f32x4 d4 = *reinterpret_cast<const f32x4*>(sLD + KV_ROWS + rowbase + 8 * a4 + 4 * g);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int i = a4 * 4 + r;
@@ -379,7 +383,7 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
     }
     // dV^T += dO^T A and dK^T += Q^T dS, 16 rows at a time; the 16 operands in the order
     // (dO^T, rows 0-15) blocks 0..3, (Q^T, rows 0-15) 0..3, (dO^T, rows 16-31), (Q^T, rows 16-31)
-#define LRSA_OPND(n) (((n) >> 2) & 1 ? read_cols_o(sQ, lo, ((n) >> 3) * 16, (n) & 3) : read_cols_o(sG, lo, ((n) >> 3) * 16, (n) & 3))
+#define LRSA_OPND(n) (((n) >> 2) & 1 ? read_cols_o(sQ, lo, rowbase + ((n) >> 3) * 16, (n) & 3) : read_cols_o(sG, lo, rowbase + ((n) >> 3) * 16, (n) & 3))
 #pragma unroll
     for (int n = 0; n < 16; ++n) {
         const int hh = n >> 3, db = n & 3;
@@ -401,8 +405,8 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
 #ifndef LRSA_DBG_NOLOAD
 #define LRSA_DBG_NOLOAD 0
 #endif
-constexpr int KV_STAGES = 4;
-constexpr int KV_LOADS_PER_STEP = 3;   // asynchronous copies one wave issues per step: 4 Q rows, 4 dO rows, lse|D
+// Two stages of 64 rows: one barrier per 64 MFMAs of a wave; the copies of the next stage run during
+// the two sub-steps of the current one.
 
 template <bool GATHER>
 __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t* __restrict__ Q,
@@ -414,14 +418,11 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
                                                              const int32_t* __restrict__ idx,
                                                              bf16_t* __restrict__ dK, bf16_t* __restrict__ dV,
                                                              float* __restrict__ part, BwdPlan P) {
-    // four stages of (Q rows, dO rows, per-wave lse|D); separate arrays so that reads of one stage
-    // need not wait for the asynchronous fill of another
-    __shared__ __attribute__((aligned(16))) unsigned char sQ0[KV_BQ * TILE_ROW_BYTES], sQ1[KV_BQ * TILE_ROW_BYTES],
-        sQ2[KV_BQ * TILE_ROW_BYTES], sQ3[KV_BQ * TILE_ROW_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char sG0[KV_BQ * TILE_ROW_BYTES], sG1[KV_BQ * TILE_ROW_BYTES],
-        sG2[KV_BQ * TILE_ROW_BYTES], sG3[KV_BQ * TILE_ROW_BYTES];
-    __shared__ __attribute__((aligned(16))) float sL0[KV_WAVES * 64], sL1[KV_WAVES * 64], sL2[KV_WAVES * 64],
-        sL3[KV_WAVES * 64];
+    // two stages of (Q rows, dO rows, per-wave lse|D); separate arrays so that reads of one stage
+    // need not wait for the asynchronous fill of the other
+    __shared__ __attribute__((aligned(16))) unsigned char sQ0[KV_ROWS * TILE_ROW_BYTES], sQ1[KV_ROWS * TILE_ROW_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sG0[KV_ROWS * TILE_ROW_BYTES], sG1[KV_ROWS * TILE_ROW_BYTES];
+    __shared__ __attribute__((aligned(16))) float sL0[KV_WAVES * 2 * KV_ROWS], sL1[KV_WAVES * 2 * KV_ROWS];
     __shared__ __attribute__((aligned(16))) unsigned char sVk[KV_BK * TILE_ROW_BYTES];   // the workgroup's V rows
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -466,22 +467,22 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
         if (key0 >= key_end) return;
         ta = key0;
     }
-    // Steps of 32 rows.  WINDOW: consecutive rows of [ta, tb).  GATHER: chunk by chunk (the last step
+    // Steps of KV_ROWS rows.  WINDOW: consecutive rows of [ta, tb).  GATHER: chunk by chunk (the last step
     // of a chunk may be partial), so that one step never sees two different gather-list prefixes.
-    const int spc = (D.L + KV_BQ - 1) / KV_BQ;                                   // GATHER: steps per chunk
-    const int sph = GATHER ? ((tb - ta + D.L - 1) / D.L) * spc : (tb - ta + KV_BQ - 1) / KV_BQ;   // steps per head
+    const int spc = (D.L + KV_ROWS - 1) / KV_ROWS;                               // GATHER: steps per chunk
+    const int sph = GATHER ? ((tb - ta + D.L - 1) / D.L) * spc : (tb - ta + KV_ROWS - 1) / KV_ROWS;   // steps per head
     const int nsteps = sph * D.G;
     // first row, row end and chunk-visible limit of a step
     auto step_rows = [&](int sidx, int& r0, int& rend, int& lim_u) {
         const int w = sidx % sph;
         if (GATHER) {
             const int c = qa + w / spc;
-            r0 = D.S + c * D.L + (w % spc) * KV_BQ;
+            r0 = D.S + c * D.L + (w % spc) * KV_ROWS;
             const int64_t e = int64_t(D.S) + int64_t(c + 1) * D.L;
             rend = e < tb ? int(e) : tb;
             lim_u = gather_count(D, c) - 1;
         } else {
-            r0 = ta + w * KV_BQ;
+            r0 = ta + w * KV_ROWS;
             rend = tb;
             lim_u = 0;
         }
@@ -512,28 +513,27 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
     const unsigned char* sVw = sVk + wave * (32 * KV_NB) * TILE_ROW_BYTES;
     const LaneOffs lo = make_lane_offs(lane);
 
-    // ---- loader: wave w fills rows 4w .. 4w+3 of the Q and dO tiles (one copy of 4 rows each) and
-    // its own lse|D block.  Steps past the end repeat the last one so that every wave always has the
-    // same number of copies in flight.
+    // ---- loader: wave w fills rows 8w .. 8w+7 of the Q and dO tiles (two copies of 4 rows each) and
+    // its own lse|D block (one copy each).
     auto issue = [&](int step, unsigned char* sQ, unsigned char* sG, float* sL) {
         if (LRSA_DBG_NOLOAD) return;
-        const int sc = step < nsteps ? step : nsteps - 1;
-        const int gi = sc / sph;
+        const int gi = step / sph;
         int r0, rend, lim_unused;
-        step_rows(sc, r0, rend, lim_unused);
+        step_rows(step, r0, rend, lim_unused);
         const int hq = h * D.G + gi;
         const int64_t base = b * D.qs[0] + hq * D.qs[1];
-        {
-            const int r4 = 4 * wave;   // 8 waves x 4 rows = the 32 rows of the step
+#pragma unroll
+        for (int i = 0; i < KV_ROWS / (4 * KV_WAVES); ++i) {
+            const int r4 = (KV_ROWS / KV_WAVES) * wave + 4 * i;
             const int row = async_row(r4, lane);
             const int t = min(r0 + row, rend - 1);
             const int64_t off = base + int64_t(t) * D.qs[2] + async_chunk(row, lane) * 8;
             async_rows4(Q + off, sQ, r4);
             async_rows4(dO + off, sG, r4);
         }
-        const int t = min(r0 + l32, rend - 1);
-        const float* src = (g ? Dsum : lse) + (int64_t(b) * D.Hq + hq) * D.n + t;
-        __builtin_amdgcn_global_load_lds((gbl_void_t*)src, (lds_void_t*)(sL + wave * 64), 4, 0, 0);
+        const int64_t rid = (int64_t(b) * D.Hq + hq) * D.n + min(r0 + lane, rend - 1);
+        __builtin_amdgcn_global_load_lds((gbl_void_t*)(lse + rid), (lds_void_t*)(sL + wave * 2 * KV_ROWS), 4, 0, 0);
+        __builtin_amdgcn_global_load_lds((gbl_void_t*)(Dsum + rid), (lds_void_t*)(sL + wave * 2 * KV_ROWS + KV_ROWS), 4, 0, 0);
     };
 
     const float c2 = D.scale * 1.4426950408889634f;
@@ -547,38 +547,35 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
 
 #define LRSA_KV_STEP(step, sQ, sG, sL, sQn, sGn, sLn)                                                   \
     {                                                                                                    \
-        wait_vmcnt<(KV_STAGES - 2) * KV_LOADS_PER_STEP>(); /* this wave's copies for `step` landed */   \
-        __syncthreads();                                     /* everybody's did; stage of step-1 free */ \
-        issue((step) + KV_STAGES - 1, sQn, sGn, sLn);                                                    \
-        int r0_, rend_, lim_u_;                                                                          \
-        step_rows(step, r0_, rend_, lim_u_);                                                             \
-        /* WINDOW: rows before the wave's first key see none of its keys.  The flag is made opaque so    */  \
-        /* that each step body stays a basic block of its own: merged into one block (or doubled into a */  \
-        /* masked and an unmasked variant) the bodies get interleaved and the register file overflows.  */  \
-        int run_ = (GATHER || r0_ + KV_BQ - 1 >= wave_key0) ? 1 : 0;                                     \
-        run_ = __builtin_amdgcn_readfirstlane(run_); /* wave-uniform by construction */                  \
-        asm volatile("" : "+s"(run_));                                                                   \
-        /* every (row, key) pair of the step visible for this wave? */                                   \
-        const bool full_ = wave_keys_valid && r0_ + KV_BQ <= rend_ &&                                    \
-                           (GATHER ? lim_u_ >= wave_key0 + 32 * KV_NB - 1 : r0_ >= wave_key0 + 32 * KV_NB - 1); \
-        if (run_ && !LRSA_DBG_NOCOMPUTE)                                                                 \
-            dkv_step<GATHER>(D, sQ, sG, sL + wave * 64, kf, sVw, lo, dk, dv, r0_, rend_, kcmp, lim_u_, !full_, c2, lane); \
+        wait_vmcnt<0>();     /* this wave's copies for `step` have landed */                             \
+        __syncthreads();     /* ... everybody's have, and everybody is done with the other stage */      \
+        if ((step) + 1 < nsteps) issue((step) + 1, sQn, sGn, sLn);                                       \
+        int r0s_, rend_, lim_u_;                                                                         \
+        step_rows(step, r0s_, rend_, lim_u_);                                                            \
+        _Pragma("unroll 1") for (int sub_ = 0; sub_ < KV_SUB; ++sub_) {                                    \
+            const int r0_ = r0s_ + sub_ * KV_BQ;                                                         \
+            /* nothing to do: padding rows only, or (WINDOW) rows before the wave's first key.  The flag */ \
+            /* is made opaque so that each sub-step body stays a basic block of its own: merged into one */ \
+            /* block the bodies get interleaved and the register file overflows.                        */ \
+            int run_ = (r0_ < rend_ && (GATHER || r0_ + KV_BQ - 1 >= wave_key0)) ? 1 : 0;                \
+            run_ = __builtin_amdgcn_readfirstlane(run_); /* wave-uniform by construction */              \
+            asm volatile("" : "+s"(run_));                                                               \
+            /* every (row, key) pair of the sub-step visible for this wave? */                           \
+            const bool full_ = wave_keys_valid && r0_ + KV_BQ <= rend_ &&                                \
+                               (GATHER ? lim_u_ >= wave_key0 + 32 * KV_NB - 1 : r0_ >= wave_key0 + 32 * KV_NB - 1); \
+            if (run_ && !LRSA_DBG_NOCOMPUTE)                                                             \
+                dkv_step<GATHER>(D, sQ, sG, sL + wave * 2 * KV_ROWS, kf, sVw, lo, dk, dv, r0_, rend_, kcmp, lim_u_, \
+                                 !full_, c2, lane, sub_ * KV_BQ);                                        \
+        }                                                                                                \
     }
 
     issue(0, sQ0, sG0, sL0);
-    issue(1, sQ1, sG1, sL1);
-    issue(2, sQ2, sG2, sL2);
-    for (int step = 0; step < nsteps; step += 4) {
-        LRSA_KV_STEP(step, sQ0, sG0, sL0, sQ3, sG3, sL3);
+    for (int step = 0; step < nsteps; step += 2) {
+        LRSA_KV_STEP(step, sQ0, sG0, sL0, sQ1, sG1, sL1);
         if (step + 1 >= nsteps) break;
         LRSA_KV_STEP(step + 1, sQ1, sG1, sL1, sQ0, sG0, sL0);
-        if (step + 2 >= nsteps) break;
-        LRSA_KV_STEP(step + 2, sQ2, sG2, sL2, sQ1, sG1, sL1);
-        if (step + 3 >= nsteps) break;
-        LRSA_KV_STEP(step + 3, sQ3, sG3, sL3, sQ2, sG2, sL2);
     }
 #undef LRSA_KV_STEP
-    wait_vmcnt<0>();   // drain the copies issued past the end before the workgroup's LDS is released
 
     const size_t part_stride = size_t(D.B) * D.Hkv * P.gl_total * 128;   // floats per slice
     const size_t part_v = size_t(P.nsl) * part_stride;                    // dV partials follow the dK partials
