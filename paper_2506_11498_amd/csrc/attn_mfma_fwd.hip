@@ -1,8 +1,8 @@
 // LRSA attention forward on bf16 MFMA (gfx950), head_dim 128: Eq. 2-3 of the paper under the
 // chunked mask, flash style (online softmax, only the log-sum-exp is kept for the backward).
 //
-// One workgroup (4 waves) owns 128 consecutive queries of one segment (the sink, or one chunk)
-// of one query head; wave w owns rows 32w .. 32w+31.  The keys those queries see form one
+// One workgroup (8 waves) owns 256 (head, query) rows: GH query heads of one KV group x 256/GH
+// consecutive queries of one segment (the sink, or one chunk); a wave owns 32 queries of one head.  The keys those queries see form one
 // stream: the gather list (sink, then the survivors of the compressed chunks) followed by the
 // contiguous local window up to the query itself.  Stream entry j is visible to query t iff
 // j <= ng + t - cs, so only the last tiles need a mask.  The stream is walked in tiles of 64
@@ -17,9 +17,9 @@
 
 namespace lrsa {
 
-constexpr int FWD_BM = 128;   // queries per workgroup
-constexpr int FWD_BN = 64;    // keys per tile
-constexpr int FWD_THREADS = 256;
+constexpr int FWD_BN = 64;     // keys per tile
+constexpr int FWD_WAVES = 8;   // waves per workgroup (two per SIMD), 32 queries each
+constexpr int FWD_THREADS = 64 * FWD_WAVES;
 
 bool mfma_supported(const Dims& D) { return D.dtype == 1 && D.d == 128; }
 size_t attn_fwd_mfma_ws_bytes(const Dims&) { return 0; }
@@ -120,12 +120,42 @@ __device__ __forceinline__ void fwd_tile(const unsigned char* sK, const unsigned
 #undef LRSA_PV
 }
 
+// Which (batch, KV head, head subset, query tile) a workgroup of a query-outer kernel takes.
+// per_unit = workgroups per (batch, KV head).  With xcd_map, consecutive workgroup ids -- which the
+// hardware deals round-robin to the 8 XCDs -- belong to 8 different KV heads, so that one XCD's L2
+// keeps serving the K/V rows of the same head.
+struct QTileMap {
+    int sink_tiles, tpc, tiles;   // query tiles of QT rows: in the sink, per chunk, per head
+    int gsubs, per_unit, xcd_map;
+};
+__device__ __forceinline__ void decode_qtile(const QTileMap& M, const Dims& D, int i, int& b, int& h, int& gsub,
+                                             int& tix) {
+    int unit, w;
+    if (M.xcd_map) {
+        const int j = i >> 3;
+        unit = (i & 7) + 8 * (j / M.per_unit);
+        w = j % M.per_unit;
+    } else {
+        unit = i / M.per_unit;
+        w = i % M.per_unit;
+    }
+    b = unit / D.Hkv;
+    h = unit % D.Hkv;
+    gsub = w % M.gsubs;
+    tix = M.tiles - 1 - w / M.gsubs;   // heaviest (latest) query tile first
+}
+
+// GH query heads of one KV group share the workgroup: its 8 waves cover GH heads x QT = 256/GH queries,
+// so every K/V tile staged in LDS serves 256 (head, query) rows.
+template <int GH>
 __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_t* __restrict__ Q,
                                                               const bf16_t* __restrict__ K,
                                                               const bf16_t* __restrict__ V,
                                                               const int32_t* __restrict__ idx,
                                                               bf16_t* __restrict__ O, float* __restrict__ lse,
-                                                              int sink_tiles, int tpc) {
+                                                              QTileMap M) {
+    constexpr int WPH = FWD_WAVES / GH;   // waves per head
+    constexpr int QT = 32 * WPH;          // queries per head and workgroup
     // two stages of (K tile, V tile); separate arrays so that reads of one stage need not wait for
     // the asynchronous fill of the other
     __shared__ __attribute__((aligned(16))) unsigned char sK0[FWD_BN * TILE_ROW_BYTES];
@@ -135,22 +165,23 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
-    const int hq = blockIdx.y, b = blockIdx.z, h = hq / D.G;
+    int b, h, gsub, tix;
+    decode_qtile(M, D, blockIdx.x, b, h, gsub, tix);
+    const int hq = h * D.G + gsub * GH + wave / WPH;
+    const int wq = wave % WPH;
 
-    // query tile, heaviest (latest) first
-    const int tix = gridDim.x - 1 - blockIdx.x;
     int qc, t0, seg_end;
-    if (tix < sink_tiles) {
-        qc = -1; t0 = tix * FWD_BM; seg_end = D.S < D.n ? D.S : D.n;
+    if (tix < M.sink_tiles) {
+        qc = -1; t0 = tix * QT; seg_end = D.S < D.n ? D.S : D.n;
     } else {
-        const int tt = tix - sink_tiles;
-        qc = tt / tpc;
-        t0 = D.S + qc * D.L + (tt % tpc) * FWD_BM;
+        const int tt = tix - M.sink_tiles;
+        qc = tt / M.tpc;
+        t0 = D.S + qc * D.L + (tt % M.tpc) * QT;
         const int64_t e = int64_t(D.S) + int64_t(qc + 1) * D.L;
         seg_end = e < D.n ? int(e) : D.n;
     }
     if (t0 >= seg_end) return;  // uniform for the workgroup
-    const int t_last = min(t0 + FWD_BM, seg_end) - 1;
+    const int t_last = min(t0 + QT, seg_end) - 1;
     const int ng = gather_count(D, qc), cs = window_start(D, qc);
     const int m_max = ng + t_last - cs + 1;           // stream entries the last row sees
     const int ntiles = (m_max + FWD_BN - 1) / FWD_BN;
@@ -160,7 +191,7 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
     const int32_t* idx_h = idx + (int64_t(b) * D.Hkv + h) * D.Ns * D.K;
 
     // this lane's query column
-    const int tq = t0 + wave * 32 + l32;
+    const int tq = t0 + wq * 32 + l32;
     const int tq_ld = tq < t_last ? tq : t_last;
     bf16x8 qf[8];
     {
@@ -169,22 +200,23 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
         for (int kk = 0; kk < 8; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + kk * 16 + g * 8);
     }
     const int lim = ng + tq - cs;                                     // last stream entry this query sees
-    const int wave_lim_max = ng + min(t0 + wave * 32 + 31, t_last) - cs;  // ... the wave's last valid query sees
+    const int wave_lim_max = ng + min(t0 + wq * 32 + 31, t_last) - cs;  // ... the wave's last valid query sees
+    const int wave_lim_min = ng + t0 + wq * 32 - cs;                    // ... the wave's first query sees
 
-    // loader: wave w fills tile rows 16w .. 16w+15 with four asynchronous copies of 4 rows each;
+    // loader: wave w fills tile rows 8w .. 8w+7 with two asynchronous copies of 4 rows each;
     // rows past the stream end re-read its last key and are masked
-    int pos[4];
+    int pos[2];
     auto fetch_pos = [&](int tile) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int j = tile * FWD_BN + async_row(16 * wave + 4 * i, lane);
+        for (int i = 0; i < 2; ++i) {
+            const int j = tile * FWD_BN + async_row(8 * wave + 4 * i, lane);
             pos[i] = stream_pos(D, idx_h, j < m_max ? j : m_max - 1, ng, cs);
         }
     };
     auto issue = [&](unsigned char* sK, unsigned char* sV) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r4 = 16 * wave + 4 * i;
+        for (int i = 0; i < 2; ++i) {
+            const int r4 = 8 * wave + 4 * i;
             const int64_t off = int64_t(pos[i]) * D.ks[2] + async_chunk(async_row(r4, lane), lane) * 8;
             async_rows4(Kh + off, sK, r4);
             async_rows4(Vh + off, sV, r4);
@@ -201,7 +233,6 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
 #pragma unroll
         for (int i = 0; i < 16; ++i) st.o[db][i] = 0.0f;
 
-    const int wave_lim_min = ng + t0 + wave * 32 - cs;   // last stream entry the wave's first query sees
 #define LRSA_FWD_TILE(sK, sV, j0_)                                                                   \
     {                                                                                                \
         const int j0 = (j0_);                                                                        \
@@ -229,7 +260,6 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
         }
         LRSA_FWD_TILE(sK1, sV1, (tile + 1) * FWD_BN);
     }
-
 #undef LRSA_FWD_TILE
 
     const float l_tot = st.l_run + __shfl_xor(st.l_run, 32, 64);
@@ -250,15 +280,35 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
     }
 }
 
+// heads of a group that share a workgroup: the largest of 4, 2, 1 that divides the group size
+static int heads_per_wg(const Dims& D) { return D.G % 4 == 0 ? 4 : D.G % 2 == 0 ? 2 : 1; }
+
+static QTileMap make_qtile_map(const Dims& D, int gh) {
+    QTileMap M;
+    const int qt = 32 * (FWD_WAVES / gh);
+    const int sink_rows = D.S < D.n ? D.S : D.n;
+    M.sink_tiles = (sink_rows + qt - 1) / qt;
+    M.tpc = (D.L + qt - 1) / qt;
+    M.tiles = M.sink_tiles + D.nq * M.tpc;
+    M.gsubs = D.G / gh;
+    M.per_unit = M.tiles * M.gsubs;
+    M.xcd_map = (D.B * D.Hkv) % 8 == 0 ? 1 : 0;
+    return M;
+}
+
 hipError_t launch_attn_fwd_mfma(const Dims& D, const void* Q, const void* K, const void* V, const int32_t* idx,
                                 void* O, float* lse, void*, hipStream_t st) {
-    const int sink_rows = D.S < D.n ? D.S : D.n;
-    const int sink_tiles = (sink_rows + FWD_BM - 1) / FWD_BM;
-    const int tpc = (D.L + FWD_BM - 1) / FWD_BM;
-    const int tiles = sink_tiles + D.nq * tpc;
-    if (tiles == 0) return hipSuccess;
-    LRSA_TIMED_LAUNCH("k_fwd_mfma", st, k_fwd_mfma, dim3(tiles, D.Hq, D.B), dim3(FWD_THREADS), 0, st, D, (const bf16_t*)Q,
-                       (const bf16_t*)K, (const bf16_t*)V, idx, (bf16_t*)O, lse, sink_tiles, tpc);
+    const int gh = heads_per_wg(D);
+    const QTileMap M = make_qtile_map(D, gh);
+    const int64_t wgs = int64_t(D.B) * D.Hkv * M.per_unit;
+    if (wgs == 0) return hipSuccess;
+    const bf16_t *q = (const bf16_t*)Q, *k = (const bf16_t*)K, *v = (const bf16_t*)V;
+    if (gh == 4)
+        LRSA_TIMED_LAUNCH("k_fwd_mfma", st, k_fwd_mfma<4>, dim3((unsigned)wgs), dim3(FWD_THREADS), 0, st, D, q, k, v, idx, (bf16_t*)O, lse, M);
+    else if (gh == 2)
+        LRSA_TIMED_LAUNCH("k_fwd_mfma", st, k_fwd_mfma<2>, dim3((unsigned)wgs), dim3(FWD_THREADS), 0, st, D, q, k, v, idx, (bf16_t*)O, lse, M);
+    else
+        LRSA_TIMED_LAUNCH("k_fwd_mfma", st, k_fwd_mfma<1>, dim3((unsigned)wgs), dim3(FWD_THREADS), 0, st, D, q, k, v, idx, (bf16_t*)O, lse, M);
     return hipGetLastError();
 }
 
