@@ -23,7 +23,9 @@ namespace lrsa {
 constexpr int BWD_THREADS = 256;
 constexpr int KV_WAVES = 8;            // waves per workgroup of the key-outer kernel (two per SIMD)
 constexpr int KV_THREADS = 64 * KV_WAVES;
-constexpr int DQ_BM = 128, DQ_BN = 64;
+constexpr int DQ_BN = 64;
+constexpr int DQ_WAVES = 8;              // waves per workgroup of the query-outer kernel (two per SIMD)
+constexpr int DQ_THREADS = 64 * DQ_WAVES;
 constexpr int KV_NB = 1;                        // 32-key blocks per wave
 constexpr int KV_BK = 32 * KV_NB * KV_WAVES;   // keys per workgroup
 constexpr int KV_BQ = 32;   // query rows per MFMA sub-step
@@ -33,7 +35,6 @@ constexpr int KV_MAX_SLICES = 16;
 
 // ------------------------------------------------------------------------------------ host-side plan
 struct BwdPlan {
-    int sink_tiles_q, tpc_q;    // dQ: query tiles of 128
     int sink_tiles_k, tpc_k;    // dK/dV window mode: key tiles of 128
     int gl_total, gtiles;       // gather list length per KV head, its tiles of 128
     int qch, nsl;               // query chunks per slice, slices per gather tile (<= KV_MAX_SLICES)
@@ -43,8 +44,6 @@ struct BwdPlan {
 static BwdPlan make_plan(const Dims& D) {
     BwdPlan P;
     const int sink_rows = D.S < D.n ? D.S : D.n;
-    P.sink_tiles_q = (sink_rows + DQ_BM - 1) / DQ_BM;
-    P.tpc_q = (D.L + DQ_BM - 1) / DQ_BM;
     P.sink_tiles_k = (sink_rows + KV_BK - 1) / KV_BK;
     P.tpc_k = (D.L + KV_BK - 1) / KV_BK;
     P.gl_total = D.nq > 0 ? D.S + D.K * D.Ns : 0;
@@ -149,14 +148,18 @@ __device__ __forceinline__ void dq_tile(const unsigned char* sK, const unsigned 
     }
 }
 
-__global__ __launch_bounds__(BWD_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t* __restrict__ Q,
-                                                            const bf16_t* __restrict__ K,
-                                                            const bf16_t* __restrict__ V,
-                                                            const bf16_t* __restrict__ dO,
-                                                            const float* __restrict__ lse,
-                                                            const float* __restrict__ Dsum,
-                                                            const int32_t* __restrict__ idx,
-                                                            bf16_t* __restrict__ dQ, int sink_tiles, int tpc) {
+// GH query heads of one KV group share the workgroup (8 waves = GH heads x 256/GH queries), as in the forward.
+template <int GH>
+__global__ __launch_bounds__(DQ_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t* __restrict__ Q,
+                                                           const bf16_t* __restrict__ K,
+                                                           const bf16_t* __restrict__ V,
+                                                           const bf16_t* __restrict__ dO,
+                                                           const float* __restrict__ lse,
+                                                           const float* __restrict__ Dsum,
+                                                           const int32_t* __restrict__ idx,
+                                                           bf16_t* __restrict__ dQ, QTileMap M) {
+    constexpr int WPH = DQ_WAVES / GH;   // waves per head
+    constexpr int QT = 32 * WPH;         // queries per head and workgroup
     __shared__ __attribute__((aligned(16))) unsigned char sK0[DQ_BN * TILE_ROW_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char sV0[DQ_BN * TILE_ROW_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char sK1[DQ_BN * TILE_ROW_BYTES];
@@ -164,21 +167,23 @@ __global__ __launch_bounds__(BWD_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t*
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
-    const int hq = blockIdx.y, b = blockIdx.z, h = hq / D.G;
+    int b, h, gsub, tix;
+    decode_qtile(M, D, blockIdx.x, b, h, gsub, tix);
+    const int hq = h * D.G + gsub * GH + wave / WPH;
+    const int wq = wave % WPH;
 
-    const int tix = gridDim.x - 1 - blockIdx.x;
     int qc, t0, seg_end;
-    if (tix < sink_tiles) {
-        qc = -1; t0 = tix * DQ_BM; seg_end = D.S < D.n ? D.S : D.n;
+    if (tix < M.sink_tiles) {
+        qc = -1; t0 = tix * QT; seg_end = D.S < D.n ? D.S : D.n;
     } else {
-        const int tt = tix - sink_tiles;
-        qc = tt / tpc;
-        t0 = D.S + qc * D.L + (tt % tpc) * DQ_BM;
+        const int tt = tix - M.sink_tiles;
+        qc = tt / M.tpc;
+        t0 = D.S + qc * D.L + (tt % M.tpc) * QT;
         const int64_t e = int64_t(D.S) + int64_t(qc + 1) * D.L;
         seg_end = e < D.n ? int(e) : D.n;
     }
     if (t0 >= seg_end) return;
-    const int t_last = min(t0 + DQ_BM, seg_end) - 1;
+    const int t_last = min(t0 + QT, seg_end) - 1;
     const int ng = gather_count(D, qc), cs = window_start(D, qc);
     const int m_max = ng + t_last - cs + 1;
     const int ntiles = (m_max + DQ_BN - 1) / DQ_BN;
@@ -187,7 +192,7 @@ __global__ __launch_bounds__(BWD_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t*
     const bf16_t* Vh = V + b * D.ks[0] + h * D.ks[1];
     const int32_t* idx_h = idx + (int64_t(b) * D.Hkv + h) * D.Ns * D.K;
 
-    const int tq = t0 + wave * 32 + l32;
+    const int tq = t0 + wq * 32 + l32;
     const int tq_ld = tq < t_last ? tq : t_last;
     const int64_t qoff = b * D.qs[0] + hq * D.qs[1] + int64_t(tq_ld) * D.qs[2];
     bf16x8 qf[8], gf[8];
@@ -200,20 +205,20 @@ __global__ __launch_bounds__(BWD_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t*
     const float lse2 = lse[rowid];   // already in log2 units
     const float Dq = Dsum[rowid];
     const int lim = ng + tq - cs;
-    const int wave_lim_max = ng + min(t0 + wave * 32 + 31, t_last) - cs;
+    const int wave_lim_max = ng + min(t0 + wq * 32 + 31, t_last) - cs;
 
-    int pos[4];
+    int pos[2];
     auto fetch_pos = [&](int tile) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int j = tile * DQ_BN + async_row(16 * wave + 4 * i, lane);
+        for (int i = 0; i < 2; ++i) {
+            const int j = tile * DQ_BN + async_row(8 * wave + 4 * i, lane);
             pos[i] = stream_pos(D, idx_h, j < m_max ? j : m_max - 1, ng, cs);
         }
     };
     auto issue = [&](unsigned char* sK, unsigned char* sV) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r4 = 16 * wave + 4 * i;
+        for (int i = 0; i < 2; ++i) {
+            const int r4 = 8 * wave + 4 * i;
             const int64_t off = int64_t(pos[i]) * D.ks[2] + async_chunk(async_row(r4, lane), lane) * 8;
             async_rows4(Kh + off, sK, r4);
             async_rows4(Vh + off, sV, r4);
@@ -222,7 +227,7 @@ __global__ __launch_bounds__(BWD_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t*
 
     const float c2 = D.scale * 1.4426950408889634f;
     const LaneOffs lo = make_lane_offs(lane);
-    const int wave_lim_min = ng + t0 + wave * 32 - cs;   // last stream entry the wave's first query sees
+    const int wave_lim_min = ng + t0 + wq * 32 - cs;   // last stream entry the wave's first query sees
 #define LRSA_DQ_TILE(sK, sV, j0_)                                                                              \
     {                                                                                                           \
         const int j0 = (j0_);                                                                                   \
@@ -657,10 +662,19 @@ hipError_t launch_attn_bwd_mfma(const Dims& D, const void* Q, const void* K, con
     LRSA_TIMED_LAUNCH("k_bwd_rowdot", st, k_bwd_rowdot, dim3((unsigned)((nrows + 15) / 16)), dim3(BWD_THREADS), 0, st, D, o, g, lse,
                       Dsum, lse2);
 
-    const int qtiles = P.sink_tiles_q + D.nq * P.tpc_q;
-    if (qtiles > 0)
-        LRSA_TIMED_LAUNCH("k_bwd_dq", st, k_bwd_dq, dim3(qtiles, D.Hq, D.B), dim3(BWD_THREADS), 0, st, D, q, k, v, g, lse2, Dsum, idx,
-                           (bf16_t*)dQ, P.sink_tiles_q, P.tpc_q);
+    {
+        const int gh = heads_per_wg(D);
+        const QTileMap M = make_qtile_map(D, gh, DQ_WAVES);
+        const int64_t wgs = int64_t(D.B) * D.Hkv * M.per_unit;
+        if (wgs > 0) {
+            if (gh == 4)
+                LRSA_TIMED_LAUNCH("k_bwd_dq", st, k_bwd_dq<4>, dim3((unsigned)wgs), dim3(DQ_THREADS), 0, st, D, q, k, v, g, lse2, Dsum, idx, (bf16_t*)dQ, M);
+            else if (gh == 2)
+                LRSA_TIMED_LAUNCH("k_bwd_dq", st, k_bwd_dq<2>, dim3((unsigned)wgs), dim3(DQ_THREADS), 0, st, D, q, k, v, g, lse2, Dsum, idx, (bf16_t*)dQ, M);
+            else
+                LRSA_TIMED_LAUNCH("k_bwd_dq", st, k_bwd_dq<1>, dim3((unsigned)wgs), dim3(DQ_THREADS), 0, st, D, q, k, v, g, lse2, Dsum, idx, (bf16_t*)dQ, M);
+        }
+    }
     if (P.gtiles > 0)
         LRSA_TIMED_LAUNCH("k_bwd_dkv_gather", st, k_bwd_dkv<true>, dim3(P.gtiles * P.nsl, D.Hkv, D.B), dim3(KV_THREADS), 0,
                           st, D, q, k, v, g, lse2, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);

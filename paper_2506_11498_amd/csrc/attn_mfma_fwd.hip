@@ -120,31 +120,6 @@ __device__ __forceinline__ void fwd_tile(const unsigned char* sK, const unsigned
 #undef LRSA_PV
 }
 
-// Which (batch, KV head, head subset, query tile) a workgroup of a query-outer kernel takes.
-// per_unit = workgroups per (batch, KV head).  With xcd_map, consecutive workgroup ids -- which the
-// hardware deals round-robin to the 8 XCDs -- belong to 8 different KV heads, so that one XCD's L2
-// keeps serving the K/V rows of the same head.
-struct QTileMap {
-    int sink_tiles, tpc, tiles;   // query tiles of QT rows: in the sink, per chunk, per head
-    int gsubs, per_unit, xcd_map;
-};
-__device__ __forceinline__ void decode_qtile(const QTileMap& M, const Dims& D, int i, int& b, int& h, int& gsub,
-                                             int& tix) {
-    int unit, w;
-    if (M.xcd_map) {
-        const int j = i >> 3;
-        unit = (i & 7) + 8 * (j / M.per_unit);
-        w = j % M.per_unit;
-    } else {
-        unit = i / M.per_unit;
-        w = i % M.per_unit;
-    }
-    b = unit / D.Hkv;
-    h = unit % D.Hkv;
-    gsub = w % M.gsubs;
-    tix = M.tiles - 1 - w / M.gsubs;   // heaviest (latest) query tile first
-}
-
 // GH query heads of one KV group share the workgroup: its 8 waves cover GH heads x QT = 256/GH queries,
 // so every K/V tile staged in LDS serves 256 (head, query) rows.
 template <int GH>
@@ -280,26 +255,10 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
     }
 }
 
-// heads of a group that share a workgroup: the largest of 4, 2, 1 that divides the group size
-static int heads_per_wg(const Dims& D) { return D.G % 4 == 0 ? 4 : D.G % 2 == 0 ? 2 : 1; }
-
-static QTileMap make_qtile_map(const Dims& D, int gh) {
-    QTileMap M;
-    const int qt = 32 * (FWD_WAVES / gh);
-    const int sink_rows = D.S < D.n ? D.S : D.n;
-    M.sink_tiles = (sink_rows + qt - 1) / qt;
-    M.tpc = (D.L + qt - 1) / qt;
-    M.tiles = M.sink_tiles + D.nq * M.tpc;
-    M.gsubs = D.G / gh;
-    M.per_unit = M.tiles * M.gsubs;
-    M.xcd_map = (D.B * D.Hkv) % 8 == 0 ? 1 : 0;
-    return M;
-}
-
 hipError_t launch_attn_fwd_mfma(const Dims& D, const void* Q, const void* K, const void* V, const int32_t* idx,
                                 void* O, float* lse, void*, hipStream_t st) {
     const int gh = heads_per_wg(D);
-    const QTileMap M = make_qtile_map(D, gh);
+    const QTileMap M = make_qtile_map(D, gh, FWD_WAVES);
     const int64_t wgs = int64_t(D.B) * D.Hkv * M.per_unit;
     if (wgs == 0) return hipSuccess;
     const bf16_t *q = (const bf16_t*)Q, *k = (const bf16_t*)K, *v = (const bf16_t*)V;
