@@ -537,8 +537,8 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
             async_rows4(dO + off, sG, r4);
         }
         const int64_t rid = (int64_t(b) * D.Hq + hq) * D.n + min(r0 + lane, rend - 1);
-        __builtin_amdgcn_global_load_lds((gbl_void_t*)(lse + rid), (lds_void_t*)(sL + wave * 2 * KV_ROWS), 4, 0, 0);
-        __builtin_amdgcn_global_load_lds((gbl_void_t*)(Dsum + rid), (lds_void_t*)(sL + wave * 2 * KV_ROWS + KV_ROWS), 4, 0, 0);
+        async_copy4(lse + rid, sL + wave * 2 * KV_ROWS);
+        async_copy4(Dsum + rid, sL + wave * 2 * KV_ROWS + KV_ROWS);
     };
 
     const float c2 = D.scale * 1.4426950408889634f;

@@ -131,12 +131,12 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
                                                               QTileMap M) {
     constexpr int WPH = FWD_WAVES / GH;   // waves per head
     constexpr int QT = 32 * WPH;          // queries per head and workgroup
-    // two stages of (K tile, V tile); separate arrays so that reads of one stage need not wait for
-    // the asynchronous fill of the other
-    __shared__ __attribute__((aligned(16))) unsigned char sK0[FWD_BN * TILE_ROW_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char sV0[FWD_BN * TILE_ROW_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char sK1[FWD_BN * TILE_ROW_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char sV1[FWD_BN * TILE_ROW_BYTES];
+    // four stages, each one array holding the K tile then the V tile; separate arrays per stage so that
+    // reads of one stage need not wait for the asynchronous fill of another (the compiler tracks only a
+    // handful of such arrays, hence K and V share one)
+    constexpr int TILE_BYTES = FWD_BN * TILE_ROW_BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char sT0[2 * TILE_BYTES], sT1[2 * TILE_BYTES], sT2[2 * TILE_BYTES],
+        sT3[2 * TILE_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
@@ -178,25 +178,42 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
     const int wave_lim_max = ng + min(t0 + wq * 32 + 31, t_last) - cs;  // ... the wave's last valid query sees
     const int wave_lim_min = ng + t0 + wq * 32 - cs;                    // ... the wave's first query sees
 
-    // loader: wave w fills tile rows 8w .. 8w+7 with two asynchronous copies of 4 rows each;
-    // rows past the stream end re-read its last key and are masked
-    int pos[2];
-    auto fetch_pos = [&](int tile) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int j = tile * FWD_BN + async_row(8 * wave + 4 * i, lane);
-            pos[i] = stream_pos(D, idx_h, j < m_max ? j : m_max - 1, ng, cs);
-        }
+    // loader: wave w fills tile rows 8w .. 8w+7 with two asynchronous copies of 4 rows each (K and V:
+    // 4 copies per tile); rows past the stream end re-read its last key and are masked.  The 8 stream
+    // positions a wave needs per tile are wave-uniform addresses, so they are fetched through the scalar
+    // cache (one iteration ahead); the only vector memory operations in the loop are the asynchronous
+    // copies, always 4 per wave and tile, which lets s_waitcnt vmcnt(n) address a tile.
+    const int32_t* idx_ld = D.Ns > 0 ? idx_h : reinterpret_cast<const int32_t*>(Kh);   // any readable words
+    const int idx_last = D.Ns > 0 ? D.Ns * D.K - 1 : 0;
+    const int wv = __builtin_amdgcn_readfirstlane(wave);
+    auto pos_entry = [&](int tc, int r) {   // clamped index into idx of row r of the wave's 8 tile rows
+        const int e = min(tc * FWD_BN + 8 * wv + r, m_max - 1) - D.S;
+        return e < 0 ? 0 : (e > idx_last ? idx_last : e);
     };
-    auto issue = [&](unsigned char* sK, unsigned char* sV) {
+    auto fetch_pos = [&](int tile, Scalar8& raw) {
+        const int tc = tile < ntiles ? tile : ntiles - 1;   // past the end: repeat the last tile (never consumed)
+        raw.a0 = smem_load(idx_ld, pos_entry(tc, 0)); raw.a1 = smem_load(idx_ld, pos_entry(tc, 1));
+        raw.a2 = smem_load(idx_ld, pos_entry(tc, 2)); raw.a3 = smem_load(idx_ld, pos_entry(tc, 3));
+        raw.a4 = smem_load(idx_ld, pos_entry(tc, 4)); raw.a5 = smem_load(idx_ld, pos_entry(tc, 5));
+        raw.a6 = smem_load(idx_ld, pos_entry(tc, 6)); raw.a7 = smem_load(idx_ld, pos_entry(tc, 7));
+    };
+    auto issue = [&](int tile, Scalar8& raw, unsigned char* sK, unsigned char* sV) {
+        const int tc = tile < ntiles ? tile : ntiles - 1;
+        const int q4 = lane >> 4;
+        smem_wait(raw);
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const int r4 = 8 * wave + 4 * i;
-            const int64_t off = int64_t(pos[i]) * D.ks[2] + async_chunk(async_row(r4, lane), lane) * 8;
+            const int r4 = 8 * wv + 4 * i;
+            int j = tc * FWD_BN + r4 + q4;
+            j = j < m_max ? j : m_max - 1;
+            const int sel = i == 0 ? pick4(q4, raw.a0, raw.a1, raw.a2, raw.a3) : pick4(q4, raw.a4, raw.a5, raw.a6, raw.a7);
+            const int pos = j < ng ? (j < D.S ? j : sel) : cs + (j - ng);
+            const int64_t off = int64_t(pos) * D.ks[2] + async_chunk(r4 + q4, lane) * 8;
             async_rows4(Kh + off, sK, r4);
             async_rows4(Vh + off, sV, r4);
         }
     };
+    constexpr int OPS_PER_TILE = 4;   // asynchronous copies per wave and tile
 
     const float c2 = D.scale * 1.4426950408889634f;  // logits are kept in log2 units
     const LaneOffs lo = make_lane_offs(lane);
@@ -215,26 +232,33 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
         else if (j0 <= wave_lim_max) fwd_tile<true>(sK, sV, qf, lo, st, j0, lim, wave_lim_max, c2, lane);          \
     }
 
-    fetch_pos(0);
-    issue(sK0, sV0);
-    if (ntiles > 1) fetch_pos(1);
-    for (int tile = 0; tile < ntiles; tile += 2) {
-        wait_vmcnt<0>();      // this wave's copies for `tile` have landed (and the next positions are here)
-        __syncthreads();      // ... everybody's have, and everybody is done with the other stage
-        if (tile + 1 < ntiles) {
-            issue(sK1, sV1);
-            if (tile + 2 < ntiles) fetch_pos(tile + 2);
-        }
-        LRSA_FWD_TILE(sK0, sV0, tile * FWD_BN);
-        if (tile + 1 >= ntiles) break;
-        wait_vmcnt<0>();
-        __syncthreads();
-        if (tile + 2 < ntiles) {
-            issue(sK0, sV0);
-            if (tile + 3 < ntiles) fetch_pos(tile + 3);
-        }
-        LRSA_FWD_TILE(sK1, sV1, (tile + 1) * FWD_BN);
+    // A wave's vector memory operations in order:  A(0) A(1) A(2) | iteration t: A(t+3)   (A = the copies
+    // of a tile).  At the top of iteration t the operations issued after A(t) are A(t+1) A(t+2).
+    Scalar8 posA, posB;
+    fetch_pos(0, posA); issue(0, posA, sT0, sT0 + TILE_BYTES);
+    fetch_pos(1, posB); issue(1, posB, sT1, sT1 + TILE_BYTES);
+    fetch_pos(2, posA); issue(2, posA, sT2, sT2 + TILE_BYTES);
+    fetch_pos(3, posB);
+    wait_all_vmem_known();   // the Q fragments (and the first tiles) are here
+#define LRSA_FWD_STEP(t_, sT, sTn, pos_use, pos_fetch)                                               \
+    {                                                                                                \
+        wait_vmcnt<2 * OPS_PER_TILE>();   /* this wave's copies for tile t_ have landed */            \
+        ring_barrier();                   /* everybody's have; everybody is done with tile t_-1 */   \
+        fetch_pos((t_) + 4, pos_fetch);                                                              \
+        issue((t_) + 3, pos_use, sTn, sTn + TILE_BYTES); /* tile t_+3 into the stage tile t_-1 used */ \
+        LRSA_FWD_TILE(sT, sT + TILE_BYTES, (t_) * FWD_BN);                                           \
     }
+    for (int tile = 0; tile < ntiles; tile += 4) {
+        LRSA_FWD_STEP(tile, sT0, sT3, posB, posA);
+        if (tile + 1 >= ntiles) break;
+        LRSA_FWD_STEP(tile + 1, sT1, sT0, posA, posB);
+        if (tile + 2 >= ntiles) break;
+        LRSA_FWD_STEP(tile + 2, sT2, sT1, posB, posA);
+        if (tile + 3 >= ntiles) break;
+        LRSA_FWD_STEP(tile + 3, sT3, sT2, posA, posB);
+    }
+#undef LRSA_FWD_STEP
+    wait_vmcnt<0>();   // copies issued past the end must land before the workgroup's LDS is released
 #undef LRSA_FWD_TILE
 
     const float l_tot = st.l_run + __shfl_xor(st.l_run, 32, 64);

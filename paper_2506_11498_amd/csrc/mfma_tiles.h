@@ -111,16 +111,84 @@ typedef __attribute__((address_space(1))) const void gbl_void_t;
 __device__ __forceinline__ int async_row(int r4, int lane) { return r4 + (lane >> 4); }
 __device__ __forceinline__ int async_chunk(int row, int lane) { return (lane & 15) ^ swz(row); }
 
+// The copies are issued through inline assembly, so the compiler does not know that LDS is written
+// behind its back: it would otherwise make LDS reads of OTHER ring stages wait for all copies in flight
+// (its alias bookkeeping for such copies is limited).  Ordering is the kernels' own business: they wait
+// with wait_vmcnt<n>() for the copies of the stage they are about to read and synchronise the workgroup.
+// Hidden operations are harmless for the compiler's own vmcnt arithmetic: vector memory loads complete in
+// order, so "at most n outstanding" still implies that everything it knows to be older has arrived.
+// M0 (the LDS base of the copy) is saved and restored around the instruction.
+__device__ __forceinline__ void async_copy16(const void* src, const void* lds_dst) {
+    const unsigned la = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lds_void_t*)lds_dst);   // wave-uniform
+    unsigned keep;
+    asm volatile(
+        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+        : "=&s"(keep)
+        : "v"(src), "s"(la)
+        : "memory");
+}
+__device__ __forceinline__ void async_copy4(const void* src, const void* lds_dst) {
+    const unsigned la = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lds_void_t*)lds_dst);
+    unsigned keep;
+    asm volatile(
+        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %1, off\n\ts_mov_b32 m0, %0"
+        : "=&s"(keep)
+        : "v"(src), "s"(la)
+        : "memory");
+}
 // src: this lane's 16 bytes in global memory; tile: LDS tile base; r4: first of the 4 rows (wave-uniform)
 __device__ __forceinline__ void async_rows4(const void* src, unsigned char* tile, int r4) {
-    __builtin_amdgcn_global_load_lds((gbl_void_t*)src, (lds_void_t*)(tile + r4 * TILE_ROW_BYTES), 16, 0, 0);
+    async_copy16(src, tile + r4 * TILE_ROW_BYTES);
 }
 
-// s_waitcnt vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14; expcnt, lgkmcnt left open)
+// s_waitcnt vmcnt(0) in the form the compiler understands: every vector memory load it has issued so far
+// (Q fragments and the like) is complete afterwards, so it will not place waits of its own for them inside
+// the ring loop, where they would also drain the asynchronous copies.
+__device__ __forceinline__ void wait_all_vmem_known() { __builtin_amdgcn_s_waitcnt((7 << 4) | (15 << 8)); }
+
+// s_waitcnt vmcnt(n) alone
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
+
+// Scalar-cache load of one 32-bit word at a wave-uniform address, issued explicitly (the compiler only
+// picks the scalar path for memory it can prove unwritten, which the asynchronous copies defeat).  The
+// result may be used only after smem_wait() on the same variables.
+__device__ __forceinline__ int smem_load(const int32_t* base, int index) {
+    int v;
+    const int off = __builtin_amdgcn_readfirstlane(index * 4);
+    asm volatile("s_load_dword %0, %1, %2" : "=s"(v) : "s"(base), "s"(off) : "memory");
+    return v;
+}
+// eight scalars (no array: indexing a private array invites the compiler to move it to memory)
+struct Scalar8 { int a0, a1, a2, a3, a4, a5, a6, a7; };
+// waits for all outstanding scalar loads (and LDS reads); ties the 8 values to the wait
+__device__ __forceinline__ void smem_wait(Scalar8& v) {
+    v.a0 = __builtin_amdgcn_readfirstlane(v.a0); v.a1 = __builtin_amdgcn_readfirstlane(v.a1);   // wave-uniform:
+    v.a2 = __builtin_amdgcn_readfirstlane(v.a2); v.a3 = __builtin_amdgcn_readfirstlane(v.a3);   // stay scalar
+    v.a4 = __builtin_amdgcn_readfirstlane(v.a4); v.a5 = __builtin_amdgcn_readfirstlane(v.a5);
+    v.a6 = __builtin_amdgcn_readfirstlane(v.a6); v.a7 = __builtin_amdgcn_readfirstlane(v.a7);
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+s"(v.a0), "+s"(v.a1), "+s"(v.a2), "+s"(v.a3), "+s"(v.a4), "+s"(v.a5), "+s"(v.a6), "+s"(v.a7)
+                 :
+                 : "memory");
+}
+// the one of four scalars that belongs to this lane's quarter q4 = lane / 16 (three conditional moves)
+__device__ __forceinline__ int pick4(int q4, int x0, int x1, int x2, int x3) {
+    int r = x0;
+    r = q4 == 1 ? x1 : r;
+    r = q4 == 2 ? x2 : r;
+    r = q4 == 3 ? x3 : r;
+    return r;
+}
+
+// Workgroup barrier without the memory fence of __syncthreads(): the fence would make the compiler wait
+// for ALL outstanding vector memory operations, i.e. also for the asynchronous copies of later ring
+// stages.  The caller has already waited (wait_vmcnt) for exactly the copies that must have landed; LDS
+// reads of the stage about to be refilled have been consumed by MFMAs before the wave gets here.  The
+// "memory" clobber keeps the compiler from moving LDS accesses across the barrier.
+__device__ __forceinline__ void ring_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 // position of stream entry j: the gather list (sink positions, then the flattened survivor
 // lists) followed by the contiguous window that starts at cs
