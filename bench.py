@@ -42,10 +42,11 @@ def pair_counts(w, local_prev=1):
     return int((gathered + window).sum()), int(gathered.sum())
 
 
-def cpu_baseline(w, x, idx_ref_holder):
-    """Time the oracle on a bounded sample: scores and selection of every head (NumPy fp32),
-    then forward + dQ of every 16th row of one KV group (C code, fp64, OpenMP)."""
-    import numpy as np
+def cpu_baseline(w, x, chunks=16):
+    """Time the oracle, as it stands, on a bounded sample: fp32 scores and selection of every head
+    (NumPy), then the whole forward and backward (every query row: O, lse, D, dQ; every key column:
+    dK, dV) of the first S + chunks*L tokens of ONE KV group in the fp64 C code with OpenMP.  The
+    method is causal, so the prefix is the same problem at a shorter length."""
     from oracle import lrsa_ref as ref
     from oracle import lrsa_rows as rows
     Kf, Vf = x["K"].float().numpy(), x["V"].float().numpy()
@@ -53,33 +54,39 @@ def cpu_baseline(w, x, idx_ref_holder):
     sc = ref.score(Kf, Vf, w.S, w.L)
     idx = ref.select(sc, w.S, w.L, w.K)
     t_sel = time.perf_counter() - t0
-    idx_ref_holder.append(idx)
     G = w.G
-    pick = np.arange(0, w.n, 16)
-    Qg, dOg = x["Q"][0, :G].float().numpy(), x["dO"][0, :G].float().numpy()
+    m = min(w.n, w.S + chunks * w.L)
+    import dataclasses
+    wp = dataclasses.replace(w, n=m)
+    ns = max(-(-(m - w.S) // w.L) - 2, 0)
+    Qg, dOg = x["Q"][0, :G, :m].float().numpy(), x["dO"][0, :G, :m].float().numpy()
     t0 = time.perf_counter()
-    rows.attn_rows(Qg, Kf[0, 0], Vf[0, 0], dOg, idx[0, 0], pick, w.S, w.L, w.K)
-    t_rows = time.perf_counter() - t0
-    t = pick
-    q = (t - w.S) // w.L
-    c = np.maximum(q - 1, 0)
-    pairs = int(np.where(t < w.S, t + 1, w.S + w.K * c + t - (w.S + w.L * c) + 1).sum())
-    flops = 8.0 * w.d * pairs * G            # logits, O, dA, dQ: 2*d flop each per pair and head
+    rows.attn_group(Qg, Kf[0, 0, :m], Vf[0, 0, :m], dOg, idx[0, 0, :ns], w.S, w.L, w.K)
+    t_attn = time.perf_counter() - t0
+    pairs, _ = pair_counts(wp)
+    pairs_full, _ = pair_counts(w)
+    flops = 14.0 * w.d * pairs * G
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return {"value": flops / t_rows / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
-            "sample": f"fp64 forward+dQ of every 16th row of KV group 0 ({len(pick)} rows x {G} heads, "
-                      f"{t_rows:.1f} s); fp32 score+select of all heads took {t_sel:.2f} s",
-            "score_select_s": t_sel}
+    t_full = t_attn * pairs_full / pairs * w.Hkv * w.B + t_sel
+    return {"value": flops / t_attn / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"fp64 forward+backward of the first {m} tokens of KV group 0 of {w.Hkv * w.B} ({G} query heads, "
+                      f"{pairs} visible pairs per head of {pairs_full}, {t_attn:.1f} s); fp32 score+select of all "
+                      f"heads at full length took {t_sel:.2f} s",
+            "attn_s": t_attn, "score_select_s": t_sel,
+            "tokens_per_s_extrapolated": w.B * w.n / t_full}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--kv-copies", type=int, default=4, help="distinct K/V copies rotated over the steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the timed steps, run one plain 1 GiB device copy (a kernel of known traffic "
+                         "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -132,6 +139,8 @@ def main():
     for name, ms in recs:
         per_kernel.setdefault(name, []).append(ms)
     kern_ms = {k: sum(v) / len(v) for k, v in per_kernel.items()}           # average launch duration
+    kern_med = {k: sorted(v)[len(v) // 2] for k, v in per_kernel.items()}
+    kern_min = {k: min(v) for k, v in per_kernel.items()}
     launches = {k: len(v) / args.steps for k, v in per_kernel.items()}
 
     pairs, pairs_g = pair_counts(w)
@@ -177,12 +186,17 @@ def main():
         "stages_ms": {"score": ms_score, "select": ms_select, "attn_fwd": ms_fwd, "attn_bwd": ms_bwd},
         "score_select": {"GBps": ss_gbps, "frac_of_hbm_peak": ss_gbps / HBM_PEAK_GBPS,
                          "algorithmic_bytes": ss_bytes},
-        "kernels_ms": kern_ms,
+        "kernels_ms": kern_ms, "kernels_ms_median": kern_med, "kernels_ms_min": kern_min,
         "roofline": roofline,
     }
+    if args.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        holder = []
-        out["cpu_baseline"] = cpu_baseline(w, x, holder)
+        out["cpu_baseline"] = cpu_baseline(w, x)
     print(json.dumps(out))
 
 
