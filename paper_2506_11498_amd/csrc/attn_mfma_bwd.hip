@@ -433,29 +433,44 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: kept in a scalar register
     const int l32 = lane & 31, g = lane >> 5;
-    const int h = blockIdx.y, b = blockIdx.z;
-    const int32_t* idx_h = idx + (int64_t(b) * D.Hkv + h) * D.Ns * D.K;
-
-    // ---- which keys, which query rows
+    // ---- which keys, which query rows.  The grid is one-dimensional and workgroup i runs on XCD i % 8
+    // (each XCD has its own L2).  GATHER: all list tiles of one (batch, KV head, query slice) stream the
+    // same Q and dO rows; they get consecutive slots of ONE XCD, so those rows are fetched from memory once
+    // per XCD, not once per tile.  WINDOW: tiles in position order, latest first, spread over the XCDs.
     int key0, key_end;   // key ids of this workgroup: positions (WINDOW) or gather-list entries (GATHER)
     int ta, tb;          // query rows [ta, tb) of every head of the group
     int qa = 0;          // GATHER: first query chunk of the slice
     int slice = 0;
+    int unit;
+    {
+        const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+        if (GATHER) {
+            const int grp = xcd + 8 * (seq / P.gtiles);
+            const int units = D.B * D.Hkv;
+            if (grp >= units * P.nsl) return;
+            unit = grp % units;
+            slice = P.nsl - 1 - grp / units;          // latest slices (most list tiles) first
+            key0 = (seq % P.gtiles) * KV_BK;
+        } else {
+            const int ktiles = P.sink_tiles_k + D.nq * P.tpc_k;
+            unit = int(blockIdx.x) / ktiles;
+            key0 = ktiles - 1 - int(blockIdx.x) % ktiles;   // tile index for now
+        }
+    }
+    const int h = unit % D.Hkv, b = unit / D.Hkv;
+    const int32_t* idx_h = idx + (int64_t(b) * D.Hkv + h) * D.Ns * D.K;
     if (GATHER) {
-        // consecutive workgroups take consecutive list tiles of ONE query slice, so the Q and dO rows
-        // they stream at the same time are the same rows (shared through L2 and the memory-side cache)
-        const int jt = blockIdx.x % P.gtiles;
-        slice = blockIdx.x / P.gtiles;
-        key0 = jt * KV_BK;
+        // slice = query chunks [slice*qch, (slice+1)*qch), of which the tile sees those from qf on
         key_end = P.gl_total;
-        qa = first_chunk_seeing(D, key0) + slice * P.qch;
-        if (qa >= D.nq) return;
-        const int qb = min(D.nq, qa + P.qch);
+        const int qf = first_chunk_seeing(D, key0);
+        qa = max(slice * P.qch, qf);
+        const int qb = min(D.nq, (slice + 1) * P.qch);
+        if (qa >= qb) return;
         ta = D.S + qa * D.L;
         const int64_t e = int64_t(D.S) + int64_t(qb) * D.L;
         tb = e < D.n ? int(e) : D.n;
     } else {
-        const int tix = gridDim.x - 1 - blockIdx.x;
+        const int tix = key0;
         if (tix < P.sink_tiles_k) {
             key0 = tix * KV_BK;
             key_end = D.S < D.n ? D.S : D.n;
@@ -574,6 +589,13 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
         }                                                                                                \
     }
 
+    // the K fragments have arrived before the first asynchronous copy is issued: the compiler then places
+    // no vector-memory waits of its own in the loop (they would also wait for the copies in flight)
+    wait_all_vmem_known();
+#pragma unroll
+    for (int nb = 0; nb < KV_NB; ++nb)
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) pin_loaded(kf[nb][kk]);
     issue(0, sQ0, sG0, sL0);
     for (int step = 0; step < nsteps; step += 2) {
         LRSA_KV_STEP(step, sQ0, sG0, sL0, sQ1, sG1, sL1);
@@ -623,9 +645,12 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
             int nrng = 0;
             const float* pk = nullptr;
             if (j >= 0) {
+                // slices that hold a partial for this entry: from the one with the first chunk that sees
+                // the entry's tile to the last
                 const int qf0 = first_chunk_seeing(D, (j / KV_BK) * KV_BK);
-                nrng = qf0 < D.nq ? (D.nq - qf0 + P.qch - 1) / P.qch : 0;
-                pk = part + ((size_t(b) * D.Hkv + h) * P.gl_total + j) * 128;
+                const int s0 = qf0 / P.qch;
+                nrng = qf0 < D.nq ? P.nsl - s0 : 0;
+                pk = part + size_t(s0) * part_stride + ((size_t(b) * D.Hkv + h) * P.gl_total + j) * 128;
             }
             const int64_t koff = b * D.ks[0] + h * D.ks[1] + int64_t(kidn) * D.ks[2];
 #pragma unroll
@@ -675,12 +700,14 @@ hipError_t launch_attn_bwd_mfma(const Dims& D, const void* Q, const void* K, con
                 LRSA_TIMED_LAUNCH("k_bwd_dq", st, k_bwd_dq<1>, dim3((unsigned)wgs), dim3(DQ_THREADS), 0, st, D, q, k, v, g, lse2, Dsum, idx, (bf16_t*)dQ, M);
         }
     }
-    if (P.gtiles > 0)
-        LRSA_TIMED_LAUNCH("k_bwd_dkv_gather", st, k_bwd_dkv<true>, dim3(P.gtiles * P.nsl, D.Hkv, D.B), dim3(KV_THREADS), 0,
+    if (P.gtiles > 0) {
+        const int64_t wgs = int64_t((D.B * D.Hkv * P.nsl + 7) / 8 * 8) * P.gtiles;
+        LRSA_TIMED_LAUNCH("k_bwd_dkv_gather", st, k_bwd_dkv<true>, dim3((unsigned)wgs), dim3(KV_THREADS), 0,
                           st, D, q, k, v, g, lse2, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
+    }
     const int ktiles = P.sink_tiles_k + D.nq * P.tpc_k;
     if (ktiles > 0)
-        LRSA_TIMED_LAUNCH("k_bwd_dkv_window", st, k_bwd_dkv<false>, dim3(ktiles, D.Hkv, D.B), dim3(KV_THREADS), 0,
+        LRSA_TIMED_LAUNCH("k_bwd_dkv_window", st, k_bwd_dkv<false>, dim3((unsigned)(int64_t(D.B) * D.Hkv * ktiles)), dim3(KV_THREADS), 0,
                           st, D, q, k, v, g, lse2, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
     return hipGetLastError();
 }

@@ -146,6 +146,14 @@ __device__ __forceinline__ void async_rows4(const void* src, unsigned char* tile
 // the ring loop, where they would also drain the asynchronous copies.
 __device__ __forceinline__ void wait_all_vmem_known() { __builtin_amdgcn_s_waitcnt((7 << 4) | (15 << 8)); }
 
+// Pins a loaded register operand at this point of the program: the empty volatile statement "uses and
+// redefines" it, so the load that produced it cannot be moved below (volatile statements keep their order,
+// and the asynchronous copies are such statements) and later uses carry no pending-load bookkeeping.
+template <class T>
+__device__ __forceinline__ void pin_loaded(T& v) {
+    asm volatile("" : "+v"(v));
+}
+
 // s_waitcnt vmcnt(n) alone
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
