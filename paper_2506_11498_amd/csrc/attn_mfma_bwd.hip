@@ -302,103 +302,74 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
     // to each read (one VALU op) instead of being kept in sixteen registers across the whole walk
     LaneOffs lo = lo_in;
     asm volatile("" : "+v"(lo.row), "+v"(lo.col));
-    // Operands are read two ahead of the MFMAs that consume them.
+    // Four MFMA groups of 8: S, dA, dV, dK.  The vector work between them is written next to MFMAs it does
+    // not depend on -- exp(S) beside the dA group, dS beside the dV group -- so that one wave keeps both
+    // pipes busy.  Operands are read two ahead of the MFMAs that consume them.
+    static_assert(KV_NB == 1, "one 32-key block per wave");
     bf16x8 a[2];
-    bf16x8 pf[KV_NB][2];   // A = exp(S - lse) as bf16 operands, 16 rows each
-    {
-        f32x16 s[KV_NB];
+    f32x16 s, dp;
 #pragma unroll
-        for (int nb = 0; nb < KV_NB; ++nb)
+    for (int i = 0; i < 16; ++i) { s[i] = 0.0f; dp[i] = 0.0f; }
+    a[0] = read_rows_o(sQ, lo, rowbase, 0);
+    a[1] = read_rows_o(sQ, lo, rowbase, 1);
 #pragma unroll
-            for (int i = 0; i < 16; ++i) s[nb][i] = 0.0f;
-        a[0] = read_rows_o(sQ, lo, rowbase, 0);
-        a[1] = read_rows_o(sQ, lo, rowbase, 1);
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-#pragma unroll
-            for (int nb = 0; nb < KV_NB; ++nb) s[nb] = mfma32(a[kk & 1], kf[nb][kk], s[nb]);
-            a[kk & 1] = kk < 6 ? read_rows_o(sQ, lo, rowbase, kk + 2) : read_rows_o(sG, lo, rowbase, kk - 6);
-        }
-        // A = exp2(S*c2 - lse2); sLD holds lse already in log2 units.  Only steps that touch the diagonal,
-        // a partly visible gather prefix, padding rows or padding keys pay for the mask (wave-uniform flag).
-        if (!need_mask) {
-#pragma unroll
-            for (int a4 = 0; a4 < 4; ++a4) {
-                const f32x4 l4 = *reinterpret_cast<const f32x4*>(sLD + rowbase + 8 * a4 + 4 * g);
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-#pragma unroll
-                    for (int nb = 0; nb < KV_NB; ++nb)
-                        s[nb][a4 * 4 + r] = fast_exp2(__builtin_fmaf(s[nb][a4 * 4 + r], c2, -l4[r]));
-            }
-        } else {
-            // row rho = 8*a4 + 4g + r of the step is visible to key block nb iff lo[nb] <= 8*a4 + r < hi
-            const int hi = (tb - r0) - 4 * g;
-            int lo[KV_NB];
-#pragma unroll
-            for (int nb = 0; nb < KV_NB; ++nb)
-                lo[nb] = GATHER ? (kcmp[nb] <= lim_u ? -64 : 64) : (kcmp[nb] == 0x7fffffff ? 64 : kcmp[nb] - r0 - 4 * g);
-#pragma unroll
-            for (int a4 = 0; a4 < 4; ++a4) {
-                const f32x4 l4 = *reinterpret_cast<const f32x4*>(sLD + rowbase + 8 * a4 + 4 * g);
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-#pragma unroll
-                    for (int nb = 0; nb < KV_NB; ++nb) {
-                        const int c = 8 * a4 + r;
-                        const float pr = fast_exp2(__builtin_fmaf(s[nb][a4 * 4 + r], c2, -l4[r]));
-                        s[nb][a4 * 4 + r] = (c >= lo[nb] && c < hi) ? pr : 0.0f;
-                    }
-            }
-        }
-#pragma unroll
-        for (int nb = 0; nb < KV_NB; ++nb) { pf[nb][0] = pack8(s[nb], 0); pf[nb][1] = pack8(s[nb], 8); }
+    for (int kk = 0; kk < 8; ++kk) {
+        s = mfma32(a[kk & 1], kf[0][kk], s);
+        a[kk & 1] = kk < 6 ? read_rows_o(sQ, lo, rowbase, kk + 2) : read_rows_o(sG, lo, rowbase, kk - 6);
     }
-    bf16x8 dsf[KV_NB][2];  // dS = A * (dA - D), the rounded A is reused
-    // dA one 32-key block after the other
+    // mask bounds: row rho = 8*a4 + 4g + r of the step is visible to the wave's key iff mlo <= 8*a4 + r < mhi
+    const int mhi = (tb - r0) - 4 * g;
+    const int mlo = GATHER ? (kcmp[0] <= lim_u ? -64 : 64) : (kcmp[0] == 0x7fffffff ? 64 : kcmp[0] - r0 - 4 * g);
+    bf16x8 vb[2];
+    vb[0] = read_rows_o(sVw, lo, 0, 0);
+    // A = exp2(S*c2 - lse2), four values per two MFMAs; sLD holds lse already in log2 units.  Only steps that
+    // touch the diagonal, a partly visible gather prefix, padding rows or padding keys pay for the mask
+    // (wave-uniform flag).
 #pragma unroll
-    for (int nb = 0; nb < KV_NB; ++nb) {
-        f32x16 dp;
+    for (int kk = 0; kk < 8; ++kk) {
+        if (kk + 1 < 8) vb[(kk + 1) & 1] = read_rows_o(sVw, lo, 0, kk + 1);
+        dp = mfma32(a[kk & 1], vb[kk & 1], dp);
+        // next operands: the rest of the dO rows, then the first transposed dO operands
+        if (kk < 6) a[kk & 1] = read_rows_o(sG, lo, rowbase, kk + 2);
+        else a[kk & 1] = read_cols_o(sG, lo, rowbase, kk - 6);
+        if ((kk & 1) == 0) {
+            const int a4 = kk >> 1;
+            const f32x4 l4 = *reinterpret_cast<const f32x4*>(sLD + rowbase + 8 * a4 + 4 * g);
+            if (!need_mask) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) dp[i] = 0.0f;
-        bf16x8 vb[2];
-        vb[0] = read_rows_o(sVw, lo, nb * 32, 0);
+                for (int r = 0; r < 4; ++r) s[a4 * 4 + r] = fast_exp2(__builtin_fmaf(s[a4 * 4 + r], c2, -l4[r]));
+            } else {
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            if (kk + 1 < 8) vb[(kk + 1) & 1] = read_rows_o(sVw, lo, nb * 32, kk + 1);
-            dp = mfma32(a[kk & 1], vb[kk & 1], dp);
-            // next operands: the rest of the dO rows, then (another block follows) the dO rows again
-            // or (last block) the first transposed dO operands
-            if (kk < 6) a[kk & 1] = read_rows_o(sG, lo, rowbase, kk + 2);
-            else if (nb + 1 < KV_NB) a[kk & 1] = read_rows_o(sG, lo, rowbase, kk - 6);
-            else a[kk & 1] = read_cols_o(sG, lo, rowbase, kk - 6);
+                for (int r = 0; r < 4; ++r) {
+                    const float pr = fast_exp2(__builtin_fmaf(s[a4 * 4 + r], c2, -l4[r]));
+                    const int c = 8 * a4 + r;
+                    s[a4 * 4 + r] = (c >= mlo && c < mhi) ? pr : 0.0f;
+                }
+            }
         }
+    }
+    bf16x8 pf[2], dsf[2];
+    pf[0] = pack8(s, 0);
+    pf[1] = pack8(s, 8);
+    // dV^T += dO^T A (rows 0-15 blocks 0..3, rows 16-31 blocks 0..3) with dS = A * (dA - D) beside it,
+    // then dK^T += Q^T dS in the same order
+#define LRSA_OPND(n) ((n) < 8 ? read_cols_o(sG, lo, rowbase + ((n) >> 2) * 16, (n) & 3) : read_cols_o(sQ, lo, rowbase + (((n) - 8) >> 2) * 16, (n) & 3))
 #pragma unroll
-        for (int a4 = 0; a4 < 4; ++a4) {
+    for (int n = 0; n < 8; ++n) {
+        dv[0][n & 3] = mfma32(a[n & 1], pf[n >> 2], dv[0][n & 3]);
+        a[n & 1] = LRSA_OPND(n + 2);
+        if ((n & 1) == 0) {
+            const int a4 = n >> 1;
             const f32x4 d4 = *reinterpret_cast<const f32x4*>(sLD + KV_ROWS + rowbase + 8 * a4 + 4 * g);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int i = a4 * 4 + r;
-                const float pr = float(pf[nb][i >> 3][i & 7]);
-                dp[i] = pr * (dp[i] - d4[r]);
-            }
+            for (int r = 0; r < 4; ++r) dp[a4 * 4 + r] = s[a4 * 4 + r] * (dp[a4 * 4 + r] - d4[r]);
         }
-        dsf[nb][0] = pack8(dp, 0);
-        dsf[nb][1] = pack8(dp, 8);
     }
-    // dV^T += dO^T A and dK^T += Q^T dS, 16 rows at a time; the 16 operands in the order
-    // (dO^T, rows 0-15) blocks 0..3, (Q^T, rows 0-15) 0..3, (dO^T, rows 16-31), (Q^T, rows 16-31)
-#define LRSA_OPND(n) (((n) >> 2) & 1 ? read_cols_o(sQ, lo, rowbase + ((n) >> 3) * 16, (n) & 3) : read_cols_o(sG, lo, rowbase + ((n) >> 3) * 16, (n) & 3))
+    dsf[0] = pack8(dp, 0);
+    dsf[1] = pack8(dp, 8);
 #pragma unroll
-    for (int n = 0; n < 16; ++n) {
-        const int hh = n >> 3, db = n & 3;
-        if ((n >> 2) & 1) {
-#pragma unroll
-            for (int nb = 0; nb < KV_NB; ++nb) dk[nb][db] = mfma32(a[n & 1], dsf[nb][hh], dk[nb][db]);
-        } else {
-#pragma unroll
-            for (int nb = 0; nb < KV_NB; ++nb) dv[nb][db] = mfma32(a[n & 1], pf[nb][hh], dv[nb][db]);
-        }
+    for (int n = 8; n < 16; ++n) {
+        dk[0][n & 3] = mfma32(a[n & 1], dsf[(n - 8) >> 2], dk[0][n & 3]);
         if (n + 2 < 16) a[n & 1] = LRSA_OPND(n + 2);
     }
 #undef LRSA_OPND
