@@ -249,41 +249,59 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_score_fused(Dims D, const T* 
         }
         __syncthreads();
     }
-    // ---- phase 2
+    // ---- phase 2: sigma of every row of chunk p; two rows of K and of V in flight per thread
     {
-        for (int z = 0; z < 2; ++z) {
-            const T* Z = (z ? Vp : Kp) + hoff;
-            float mn[VEC], den[VEC], inv[VEC];
+        float mn[2][VEC], den[2][VEC], inv[2][VEC];
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) { mn[i] = s_mn[z][sub * VEC + i]; den[i] = s_den[z][sub * VEC + i]; inv[i] = s_inv[z][sub * VEC + i]; }
-            for (int r = rg; r < D.L; r += 2 * rpp) {
-                const bool has2 = r + rpp < D.L;
-                const int r2 = has2 ? r + rpp : r;
-                float x0[VEC], x1[VEC];
-                Elem<T>::load(Z + (cur0 + r) * D.ks[2] + sub * VEC, x0);
-                Elem<T>::load(Z + (cur0 + r2) * D.ks[2] + sub * VEC, x1);
-                float s0 = 0.0f, s1 = 0.0f;
+        for (int z = 0; z < 2; ++z)
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) {
-                    const float a0 = x0[i] - mn[i], a1 = x1[i] - mn[i];
-                    float q0 = a0 * inv[i], q1 = a1 * inv[i];
-                    q0 = __builtin_fmaf(__builtin_fmaf(-den[i], q0, a0), inv[i], q0);
-                    q1 = __builtin_fmaf(__builtin_fmaf(-den[i], q1, a1), inv[i], q1);
-                    x0[i] = q0; x1[i] = q1;
-                    s0 += q0; s1 += q1;
-                }
-                for (int o = lpr >> 1; o > 0; o >>= 1) { s0 += __shfl_xor(s0, o, 64); s1 += __shfl_xor(s1, o, 64); }
-                const float m0 = s0 / float(D.d), m1 = s1 / float(D.d);
-                float v0 = 0.0f, v1 = 0.0f;
+            for (int i = 0; i < VEC; ++i) {
+                mn[z][i] = s_mn[z][sub * VEC + i]; den[z][i] = s_den[z][sub * VEC + i]; inv[z][i] = s_inv[z][sub * VEC + i];
+            }
+        for (int r = rg; r < D.L; r += 2 * rpp) {
+            const bool has2 = r + rpp < D.L;
+            const int r2 = has2 ? r + rpp : r;
+            float x[4][VEC];   // K row r, K row r2, V row r, V row r2
+            Elem<T>::load(Kp + hoff + (cur0 + r) * D.ks[2] + sub * VEC, x[0]);
+            Elem<T>::load(Kp + hoff + (cur0 + r2) * D.ks[2] + sub * VEC, x[1]);
+            Elem<T>::load(Vp + hoff + (cur0 + r) * D.ks[2] + sub * VEC, x[2]);
+            Elem<T>::load(Vp + hoff + (cur0 + r2) * D.ks[2] + sub * VEC, x[3]);
+            float sm4[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int z = j >> 1;
+                float acc = 0.0f;
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) {
-                    const float d0 = x0[i] - m0, d1 = x1[i] - m1;
-                    v0 += d0 * d0; v1 += d1 * d1;
+                    const float a0 = x[j][i] - mn[z][i];
+                    float q0 = a0 * inv[z][i];
+                    q0 = __builtin_fmaf(__builtin_fmaf(-den[z][i], q0, a0), inv[z][i], q0);   // correctly rounded a0 / den
+                    x[j][i] = q0;
+                    acc += q0;
                 }
-                for (int o = lpr >> 1; o > 0; o >>= 1) { v0 += __shfl_xor(v0, o, 64); v1 += __shfl_xor(v1, o, 64); }
-                if (sub == 0) {
-                    sig[z][r] = sqrtf(v0 / float(D.d - D.ddof));
-                    if (has2) sig[z][r2] = sqrtf(v1 / float(D.d - D.ddof));
+                sm4[j] = acc;
+            }
+            for (int o = lpr >> 1; o > 0; o >>= 1)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sm4[j] += __shfl_xor(sm4[j], o, 64);
+            float var4[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float m = sm4[j] / float(D.d);
+                float acc = 0.0f;
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) { const float dd = x[j][i] - m; acc += dd * dd; }
+                var4[j] = acc;
+            }
+            for (int o = lpr >> 1; o > 0; o >>= 1)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) var4[j] += __shfl_xor(var4[j], o, 64);
+            if (sub == 0) {
+                sig[0][r] = sqrtf(var4[0] / float(D.d - D.ddof));
+                sig[1][r] = sqrtf(var4[2] / float(D.d - D.ddof));
+                if (has2) {
+                    sig[0][r2] = sqrtf(var4[1] / float(D.d - D.ddof));
+                    sig[1][r2] = sqrtf(var4[3] / float(D.d - D.ddof));
                 }
             }
         }
