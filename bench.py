@@ -148,8 +148,7 @@ def main():
     flops_step = 14.0 * unit * pairs
     # algorithmic flops per launch: forward 4*d per pair; backward 10*d per pair = S, dA, dV, dK
     # (8*d, in the key-outer kernels) + dQ (2*d, in the query-outer kernel)
-    kern_flops = {"k_fwd_mfma": 4.0 * unit * pairs, "k_bwd_dq": 2.0 * unit * pairs,
-                  "k_bwd_dkv_gather": 8.0 * unit * pairs_g, "k_bwd_dkv_window": 8.0 * unit * (pairs - pairs_g)}
+    kern_flops = {"k_fwd_mfma": 4.0 * unit * pairs, "k_bwd_dq": 2.0 * unit * pairs, "k_bwd_dkv": 8.0 * unit * pairs}
     cand = [k for k in kern_flops if k in kern_ms]
     roofline = None
     if cand:
@@ -170,7 +169,7 @@ def main():
     ms_score = stage(["k_score_fused", "k_minmaxT", "k_sigmaT", "k_softmax"])
     ms_select = stage(["k_select"])
     ms_fwd = stage(["k_fwd_mfma", "k_fwd_genericT"])
-    ms_bwd = stage(["k_bwd_rowdot", "k_bwd_dq", "k_bwd_dkv_gather", "k_bwd_dkv_window", "k_bwd_dq_genericT", "k_bwd_dkv_genericT"])
+    ms_bwd = stage(["k_bwd_rowdot", "k_bwd_dq", "k_bwd_dkv", "k_bwd_dkv_reduce", "k_bwd_dq_genericT", "k_bwd_dkv_genericT"])
     ss_bytes = score_bytes + 4 * w.B * w.Hkv * Ns * w.K     # K and V read once, scores and idx written once
     ss_gbps = ss_bytes / max(ms_score + ms_select, 1e-9) / 1e6
     out = {

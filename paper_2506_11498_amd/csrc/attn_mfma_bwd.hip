@@ -21,12 +21,18 @@
 namespace lrsa {
 
 constexpr int BWD_THREADS = 256;
-constexpr int KV_WAVES = 8;            // waves per workgroup of the key-outer kernel (two per SIMD)
+#ifndef LRSA_KV_WAVES
+#define LRSA_KV_WAVES 8
+#endif
+#ifndef LRSA_KV_NB
+#define LRSA_KV_NB 1
+#endif
+constexpr int KV_WAVES = LRSA_KV_WAVES;   // waves per workgroup of the key-outer kernel
 constexpr int KV_THREADS = 64 * KV_WAVES;
 constexpr int DQ_BN = 64;
 constexpr int DQ_WAVES = 8;              // waves per workgroup of the query-outer kernel (two per SIMD)
 constexpr int DQ_THREADS = 64 * DQ_WAVES;
-constexpr int KV_NB = 1;                        // 32-key blocks per wave
+constexpr int KV_NB = LRSA_KV_NB;               // 32-key blocks per wave
 constexpr int KV_BK = 32 * KV_NB * KV_WAVES;   // keys per workgroup
 constexpr int KV_BQ = 32;   // query rows per MFMA sub-step
 constexpr int KV_SUB = 2;   // sub-steps per pipeline step (one LDS stage, one barrier)
@@ -38,6 +44,7 @@ struct BwdPlan {
     int sink_tiles_k, tpc_k;    // dK/dV window mode: key tiles of 128
     int gl_total, gtiles;       // gather list length per KV head, its tiles of 128
     int qch, nsl;               // query chunks per slice, slices per gather tile (<= KV_MAX_SLICES)
+    int gather_wgs;             // workgroups of the GATHER part of the dK/dV launch (a multiple of 8)
     size_t off_lse2, off_part, bytes;   // workspace: D, lse in log2 units, then the fp32 partials
 };
 
@@ -58,7 +65,9 @@ static BwdPlan make_plan(const Dims& D) {
     P.nsl = D.nq > 0 ? (D.nq + P.qch - 1) / P.qch : 0;
     P.off_lse2 = align256(size_t(D.B) * D.Hq * D.n * 4);
     P.off_part = 2 * P.off_lse2;
-    const size_t part = size_t(2) * P.nsl * D.B * D.Hkv * P.gl_total * 128 * 4;
+    P.gather_wgs = P.gtiles > 0 ? (D.B * D.Hkv * P.nsl + 7) / 8 * 8 * P.gtiles : 0;
+    // slots 0 .. nsl-1: the GATHER workgroups' slices; slot nsl: what the WINDOW workgroups add to listed positions
+    const size_t part = size_t(2) * (P.nsl + 1) * D.B * D.Hkv * P.gl_total * 128 * 4;
     P.bytes = P.off_part + align256(part);
     return P;
 }
@@ -302,33 +311,43 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
     // to each read (one VALU op) instead of being kept in sixteen registers across the whole walk
     LaneOffs lo = lo_in;
     asm volatile("" : "+v"(lo.row), "+v"(lo.col));
-    // Four MFMA groups of 8: S, dA, dV, dK.  The vector work between them is written next to MFMAs it does
-    // not depend on -- exp(S) beside the dA group, dS beside the dV group -- so that one wave keeps both
-    // pipes busy.  Operands are read two ahead of the MFMAs that consume them.
-    static_assert(KV_NB == 1, "one 32-key block per wave");
+    // Four MFMA groups: S, dA, dV, dK (8 MFMAs per 32-key block each).  The vector work between them is
+    // written next to MFMAs it does not depend on -- exp(S) beside the dA group, dS beside the dV group --
+    // so that one wave keeps both pipes busy.  Operands are read two ahead of the MFMAs that consume them;
+    // an operand read from the Q / dO stage serves all key blocks of the wave.
     bf16x8 a[2];
-    f32x16 s, dp;
+    f32x16 s[KV_NB], dp[KV_NB];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { s[i] = 0.0f; dp[i] = 0.0f; }
+    for (int nb = 0; nb < KV_NB; ++nb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { s[nb][i] = 0.0f; dp[nb][i] = 0.0f; }
     a[0] = read_rows_o(sQ, lo, rowbase, 0);
     a[1] = read_rows_o(sQ, lo, rowbase, 1);
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
-        s = mfma32(a[kk & 1], kf[0][kk], s);
+#pragma unroll
+        for (int nb = 0; nb < KV_NB; ++nb) s[nb] = mfma32(a[kk & 1], kf[nb][kk], s[nb]);
         a[kk & 1] = kk < 6 ? read_rows_o(sQ, lo, rowbase, kk + 2) : read_rows_o(sG, lo, rowbase, kk - 6);
     }
-    // mask bounds: row rho = 8*a4 + 4g + r of the step is visible to the wave's key iff mlo <= 8*a4 + r < mhi
+    // mask bounds: row rho = 8*a4 + 4g + r of the step is visible to key block nb iff mlo[nb] <= 8*a4 + r < mhi
     const int mhi = (tb - r0) - 4 * g;
-    const int mlo = GATHER ? (kcmp[0] <= lim_u ? -64 : 64) : (kcmp[0] == 0x7fffffff ? 64 : kcmp[0] - r0 - 4 * g);
-    bf16x8 vb[2];
-    vb[0] = read_rows_o(sVw, lo, 0, 0);
-    // A = exp2(S*c2 - lse2), four values per two MFMAs; sLD holds lse already in log2 units.  Only steps that
-    // touch the diagonal, a partly visible gather prefix, padding rows or padding keys pay for the mask
-    // (wave-uniform flag).
+    int mlo[KV_NB];
+#pragma unroll
+    for (int nb = 0; nb < KV_NB; ++nb)
+        mlo[nb] = GATHER ? (kcmp[nb] <= lim_u ? -64 : 64) : (kcmp[nb] == 0x7fffffff ? 64 : kcmp[nb] - r0 - 4 * g);
+    // A = exp2(S*c2 - lse2), four values per key block and pair of MFMA rounds; sLD holds lse already in
+    // log2 units.  Only steps that touch the diagonal, a partly visible gather prefix, padding rows or
+    // padding keys pay for the mask (wave-uniform flag).
+    bf16x8 vb[KV_NB][2];
+#pragma unroll
+    for (int nb = 0; nb < KV_NB; ++nb) vb[nb][0] = read_rows_o(sVw, lo, nb * 32, 0);
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
-        if (kk + 1 < 8) vb[(kk + 1) & 1] = read_rows_o(sVw, lo, 0, kk + 1);
-        dp = mfma32(a[kk & 1], vb[kk & 1], dp);
+#pragma unroll
+        for (int nb = 0; nb < KV_NB; ++nb) {
+            if (kk + 1 < 8) vb[nb][(kk + 1) & 1] = read_rows_o(sVw, lo, nb * 32, kk + 1);
+            dp[nb] = mfma32(a[kk & 1], vb[nb][kk & 1], dp[nb]);
+        }
         // next operands: the rest of the dO rows, then the first transposed dO operands
         if (kk < 6) a[kk & 1] = read_rows_o(sG, lo, rowbase, kk + 2);
         else a[kk & 1] = read_cols_o(sG, lo, rowbase, kk - 6);
@@ -337,39 +356,48 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
             const f32x4 l4 = *reinterpret_cast<const f32x4*>(sLD + rowbase + 8 * a4 + 4 * g);
             if (!need_mask) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) s[a4 * 4 + r] = fast_exp2(__builtin_fmaf(s[a4 * 4 + r], c2, -l4[r]));
+                for (int nb = 0; nb < KV_NB; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        s[nb][a4 * 4 + r] = fast_exp2(__builtin_fmaf(s[nb][a4 * 4 + r], c2, -l4[r]));
             } else {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float pr = fast_exp2(__builtin_fmaf(s[a4 * 4 + r], c2, -l4[r]));
-                    const int c = 8 * a4 + r;
-                    s[a4 * 4 + r] = (c >= mlo && c < mhi) ? pr : 0.0f;
-                }
+                for (int nb = 0; nb < KV_NB; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float pr = fast_exp2(__builtin_fmaf(s[nb][a4 * 4 + r], c2, -l4[r]));
+                        const int c = 8 * a4 + r;
+                        s[nb][a4 * 4 + r] = (c >= mlo[nb] && c < mhi) ? pr : 0.0f;
+                    }
             }
         }
     }
-    bf16x8 pf[2], dsf[2];
-    pf[0] = pack8(s, 0);
-    pf[1] = pack8(s, 8);
+    bf16x8 pf[KV_NB][2], dsf[KV_NB][2];
+#pragma unroll
+    for (int nb = 0; nb < KV_NB; ++nb) { pf[nb][0] = pack8(s[nb], 0); pf[nb][1] = pack8(s[nb], 8); }
     // dV^T += dO^T A (rows 0-15 blocks 0..3, rows 16-31 blocks 0..3) with dS = A * (dA - D) beside it,
     // then dK^T += Q^T dS in the same order
 #define LRSA_OPND(n) ((n) < 8 ? read_cols_o(sG, lo, rowbase + ((n) >> 2) * 16, (n) & 3) : read_cols_o(sQ, lo, rowbase + (((n) - 8) >> 2) * 16, (n) & 3))
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
-        dv[0][n & 3] = mfma32(a[n & 1], pf[n >> 2], dv[0][n & 3]);
+#pragma unroll
+        for (int nb = 0; nb < KV_NB; ++nb) dv[nb][n & 3] = mfma32(a[n & 1], pf[nb][n >> 2], dv[nb][n & 3]);
         a[n & 1] = LRSA_OPND(n + 2);
         if ((n & 1) == 0) {
             const int a4 = n >> 1;
             const f32x4 d4 = *reinterpret_cast<const f32x4*>(sLD + KV_ROWS + rowbase + 8 * a4 + 4 * g);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) dp[a4 * 4 + r] = s[a4 * 4 + r] * (dp[a4 * 4 + r] - d4[r]);
+            for (int nb = 0; nb < KV_NB; ++nb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) dp[nb][a4 * 4 + r] = s[nb][a4 * 4 + r] * (dp[nb][a4 * 4 + r] - d4[r]);
         }
     }
-    dsf[0] = pack8(dp, 0);
-    dsf[1] = pack8(dp, 8);
+#pragma unroll
+    for (int nb = 0; nb < KV_NB; ++nb) { dsf[nb][0] = pack8(dp[nb], 0); dsf[nb][1] = pack8(dp[nb], 8); }
 #pragma unroll
     for (int n = 8; n < 16; ++n) {
-        dk[0][n & 3] = mfma32(a[n & 1], dsf[(n - 8) >> 2], dk[0][n & 3]);
+#pragma unroll
+        for (int nb = 0; nb < KV_NB; ++nb) dk[nb][n & 3] = mfma32(a[n & 1], dsf[nb][(n - 8) >> 2], dk[nb][n & 3]);
         if (n + 2 < 16) a[n & 1] = LRSA_OPND(n + 2);
     }
 #undef LRSA_OPND
@@ -384,22 +412,33 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
 // Two stages of 64 rows: one barrier per 64 MFMAs of a wave; the copies of the next stage run during
 // the two sub-steps of the current one.
 
-template <bool GATHER>
-__global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t* __restrict__ Q,
-                                                             const bf16_t* __restrict__ K,
-                                                             const bf16_t* __restrict__ V,
-                                                             const bf16_t* __restrict__ dO,
-                                                             const float* __restrict__ lse,
-                                                             const float* __restrict__ Dsum,
-                                                             const int32_t* __restrict__ idx,
-                                                             bf16_t* __restrict__ dK, bf16_t* __restrict__ dV,
-                                                             float* __restrict__ part, BwdPlan P) {
-    // two stages of (Q rows, dO rows, per-wave lse|D); separate arrays so that reads of one stage
-    // need not wait for the asynchronous fill of the other
+// LDS of the dK/dV kernel: two stages of (Q rows, dO rows, per-wave lse|D) -- separate arrays so that reads
+// of one stage need not wait for the asynchronous fill of the other -- and the workgroup's V rows
+struct KvLds {
+    unsigned char *sQ0, *sQ1, *sG0, *sG1;
+    float *sL0, *sL1;
+    unsigned char* sVk;
+};
+// one set of arrays for both instantiations of the body (a template would get a set each)
+__device__ __forceinline__ KvLds kv_lds() {
     __shared__ __attribute__((aligned(16))) unsigned char sQ0[KV_ROWS * TILE_ROW_BYTES], sQ1[KV_ROWS * TILE_ROW_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char sG0[KV_ROWS * TILE_ROW_BYTES], sG1[KV_ROWS * TILE_ROW_BYTES];
     __shared__ __attribute__((aligned(16))) float sL0[KV_WAVES * 2 * KV_ROWS], sL1[KV_WAVES * 2 * KV_ROWS];
-    __shared__ __attribute__((aligned(16))) unsigned char sVk[KV_BK * TILE_ROW_BYTES];   // the workgroup's V rows
+    __shared__ __attribute__((aligned(16))) unsigned char sVk[KV_BK * TILE_ROW_BYTES];
+    return KvLds{sQ0, sQ1, sG0, sG1, sL0, sL1, sVk};
+}
+
+template <bool GATHER>
+__device__ __forceinline__ void dkv_body(const Dims& D, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                         const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO,
+                                         const float* __restrict__ lse, const float* __restrict__ Dsum,
+                                         const int32_t* __restrict__ idx, bf16_t* __restrict__ dK,
+                                         bf16_t* __restrict__ dV, float* __restrict__ part, const BwdPlan& P,
+                                         const int block) {
+    const KvLds sh = kv_lds();
+    unsigned char *const sQ0 = sh.sQ0, *const sQ1 = sh.sQ1, *const sG0 = sh.sG0, *const sG1 = sh.sG1;
+    float *const sL0 = sh.sL0, *const sL1 = sh.sL1;
+    unsigned char* const sVk = sh.sVk;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: kept in a scalar register
@@ -414,7 +453,7 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
     int slice = 0;
     int unit;
     {
-        const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+        const int xcd = block & 7, seq = block >> 3;
         if (GATHER) {
             const int grp = xcd + 8 * (seq / P.gtiles);
             const int units = D.B * D.Hkv;
@@ -424,8 +463,8 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
             key0 = (seq % P.gtiles) * KV_BK;
         } else {
             const int ktiles = P.sink_tiles_k + D.nq * P.tpc_k;
-            unit = int(blockIdx.x) / ktiles;
-            key0 = ktiles - 1 - int(blockIdx.x) % ktiles;   // tile index for now
+            unit = block / ktiles;
+            key0 = ktiles - 1 - block % ktiles;   // tile index for now
         }
     }
     const int h = unit % D.Hkv, b = unit / D.Hkv;
@@ -576,7 +615,7 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
 #undef LRSA_KV_STEP
 
     const size_t part_stride = size_t(D.B) * D.Hkv * P.gl_total * 128;   // floats per slice
-    const size_t part_v = size_t(P.nsl) * part_stride;                    // dV partials follow the dK partials
+    const size_t part_v = size_t(P.nsl + 1) * part_stride;                // dV partials follow the dK partials
 #pragma unroll
     for (int nb = 0; nb < KV_NB; ++nb) {
         const int kidn = key0 + wave * (32 * KV_NB) + nb * 32 + (lane & 31);
@@ -613,17 +652,9 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
                     }
                 }
             }
-            int nrng = 0;
-            const float* pk = nullptr;
-            if (j >= 0) {
-                // slices that hold a partial for this entry: from the one with the first chunk that sees
-                // the entry's tile to the last
-                const int qf0 = first_chunk_seeing(D, (j / KV_BK) * KV_BK);
-                const int s0 = qf0 / P.qch;
-                nrng = qf0 < D.nq ? P.nsl - s0 : 0;
-                pk = part + size_t(s0) * part_stride + ((size_t(b) * D.Hkv + h) * P.gl_total + j) * 128;
-            }
             const int64_t koff = b * D.ks[0] + h * D.ks[1] + int64_t(kidn) * D.ks[2];
+            // listed positions: fp32 into the extra slot, the reduction kernel adds the slices; others: final
+            float* pk = j >= 0 ? part + size_t(P.nsl) * part_stride + ((size_t(b) * D.Hkv + h) * P.gl_total + j) * 128 : nullptr;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -632,15 +663,62 @@ __global__ __launch_bounds__(KV_THREADS, 2) void k_bwd_dkv(Dims D, const bf16_t*
 #pragma unroll
                     for (int r = 0; r < 4; ++r) { x[r] = dk[nb][db][a * 4 + r] * D.scale; y[r] = dv[nb][db][a * 4 + r]; }
                     const int dcol = db * 32 + a * 8 + g * 4;
-                    for (int sidx = 0; sidx < nrng; ++sidx) {
-                        x += *reinterpret_cast<const f32x4*>(pk + size_t(sidx) * part_stride + dcol);
-                        y += *reinterpret_cast<const f32x4*>(pk + part_v + size_t(sidx) * part_stride + dcol);
+                    if (j >= 0) {
+                        *reinterpret_cast<f32x4*>(pk + dcol) = x;
+                        *reinterpret_cast<f32x4*>(pk + part_v + dcol) = y;
+                    } else {
+                        *reinterpret_cast<bf16x4*>(dK + koff + dcol) = __builtin_convertvector(x, bf16x4);
+                        *reinterpret_cast<bf16x4*>(dV + koff + dcol) = __builtin_convertvector(y, bf16x4);
                     }
-                    *reinterpret_cast<bf16x4*>(dK + koff + dcol) = __builtin_convertvector(x, bf16x4);
-                    *reinterpret_cast<bf16x4*>(dV + koff + dcol) = __builtin_convertvector(y, bf16x4);
                 }
         }
     }
+}
+
+// One launch for all of dK/dV: the GATHER workgroups first (equal, long), then the WINDOW workgroups, so that
+// the chip has one tail, not two.
+__global__ __launch_bounds__(KV_THREADS, KV_WAVES == 8 ? 2 : 1) void k_bwd_dkv(Dims D, const bf16_t* __restrict__ Q,
+                                                                                const bf16_t* __restrict__ K,
+                                                                                const bf16_t* __restrict__ V,
+                                                                                const bf16_t* __restrict__ dO,
+                                                                                const float* __restrict__ lse,
+                                                                                const float* __restrict__ Dsum,
+                                                                                const int32_t* __restrict__ idx,
+                                                                                bf16_t* __restrict__ dK,
+                                                                                bf16_t* __restrict__ dV,
+                                                                                float* __restrict__ part, BwdPlan P) {
+    const int block = blockIdx.x;
+    if (block < P.gather_wgs) dkv_body<true>(D, Q, K, V, dO, lse, Dsum, idx, dK, dV, part, P, block);
+    else dkv_body<false>(D, Q, K, V, dO, lse, Dsum, idx, dK, dV, part, P, block - P.gather_wgs);
+}
+
+// dK, dV of the listed positions (sink tokens and survivors): the WINDOW contribution plus the GATHER slices
+// that exist for the entry's list tile, added in a fixed order.  32 threads per entry, 4 channels each.
+__global__ __launch_bounds__(256) void k_bwd_dkv_reduce(Dims D, const int32_t* __restrict__ idx,
+                                                        const float* __restrict__ part, bf16_t* __restrict__ dK,
+                                                        bf16_t* __restrict__ dV, BwdPlan P) {
+    const int64_t e = int64_t(blockIdx.x) * 8 + (threadIdx.x >> 5);   // (b, h, entry)
+    const int64_t total = int64_t(D.B) * D.Hkv * P.gl_total;
+    if (e >= total) return;
+    const int j = int(e % P.gl_total);
+    const int bh = int(e / P.gl_total);
+    const int b = bh / D.Hkv, h = bh % D.Hkv;
+    const int pos = j < D.S ? j : idx[(int64_t(bh) * D.Ns) * D.K + (j - D.S)];
+    const size_t part_stride = size_t(D.B) * D.Hkv * P.gl_total * 128;
+    const size_t part_v = size_t(P.nsl + 1) * part_stride;
+    const int dcol = (threadIdx.x & 31) * 4;
+    const float* p0 = part + size_t(e) * 128 + dcol;
+    f32x4 x = *reinterpret_cast<const f32x4*>(p0 + size_t(P.nsl) * part_stride);
+    f32x4 y = *reinterpret_cast<const f32x4*>(p0 + size_t(P.nsl) * part_stride + part_v);
+    const int qf0 = first_chunk_seeing(D, (j / KV_BK) * KV_BK);
+    if (qf0 < D.nq)
+        for (int sl = qf0 / P.qch; sl < P.nsl; ++sl) {
+            x += *reinterpret_cast<const f32x4*>(p0 + size_t(sl) * part_stride);
+            y += *reinterpret_cast<const f32x4*>(p0 + size_t(sl) * part_stride + part_v);
+        }
+    const int64_t koff = b * D.ks[0] + h * D.ks[1] + int64_t(pos) * D.ks[2];
+    *reinterpret_cast<bf16x4*>(dK + koff + dcol) = __builtin_convertvector(x, bf16x4);
+    *reinterpret_cast<bf16x4*>(dV + koff + dcol) = __builtin_convertvector(y, bf16x4);
 }
 
 // ------------------------------------------------------------------------------------ launcher
@@ -671,15 +749,15 @@ hipError_t launch_attn_bwd_mfma(const Dims& D, const void* Q, const void* K, con
                 LRSA_TIMED_LAUNCH("k_bwd_dq", st, k_bwd_dq<1>, dim3((unsigned)wgs), dim3(DQ_THREADS), 0, st, D, q, k, v, g, lse2, Dsum, idx, (bf16_t*)dQ, M);
         }
     }
-    if (P.gtiles > 0) {
-        const int64_t wgs = int64_t((D.B * D.Hkv * P.nsl + 7) / 8 * 8) * P.gtiles;
-        LRSA_TIMED_LAUNCH("k_bwd_dkv_gather", st, k_bwd_dkv<true>, dim3((unsigned)wgs), dim3(KV_THREADS), 0,
-                          st, D, q, k, v, g, lse2, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
-    }
     const int ktiles = P.sink_tiles_k + D.nq * P.tpc_k;
-    if (ktiles > 0)
-        LRSA_TIMED_LAUNCH("k_bwd_dkv_window", st, k_bwd_dkv<false>, dim3((unsigned)(int64_t(D.B) * D.Hkv * ktiles)), dim3(KV_THREADS), 0,
-                          st, D, q, k, v, g, lse2, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
+    const int64_t wgs = int64_t(P.gather_wgs) + int64_t(D.B) * D.Hkv * ktiles;
+    if (wgs > 0)
+        LRSA_TIMED_LAUNCH("k_bwd_dkv", st, k_bwd_dkv, dim3((unsigned)wgs), dim3(KV_THREADS), 0, st, D, q, k, v, g, lse2,
+                          Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
+    const int64_t entries = int64_t(D.B) * D.Hkv * P.gl_total;
+    if (entries > 0)
+        LRSA_TIMED_LAUNCH("k_bwd_dkv_reduce", st, k_bwd_dkv_reduce, dim3((unsigned)((entries + 7) / 8)), dim3(256), 0, st, D,
+                          idx, part, (bf16_t*)dK, (bf16_t*)dV, P);
     return hipGetLastError();
 }
 
