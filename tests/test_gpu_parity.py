@@ -84,6 +84,13 @@ SMALL = [
     dict(name="bf16_d128_gqa", n=16 + 6 * 64 + 40, L=64, S=16, K=16, d=128, Hq=8, Hkv=2, B=2, dtype="bf16"),
     dict(name="bf16_odd_sizes", n=5 + 7 * 100 + 33, L=100, S=5, K=37, d=128, Hq=2, Hkv=1, B=1, dtype="bf16"),
     dict(name="bf16_long_tiles", n=64 + 4 * 512 + 300, L=512, S=64, K=128, d=128, Hq=2, Hkv=1, B=1, dtype="bf16"),
+    # degenerate cases on the MFMA path (bf16, d 128)
+    dict(name="mfma_sink_only", n=40, L=32, S=64, K=8, d=128, Hq=2, Hkv=1, B=1, dtype="bf16"),
+    dict(name="mfma_one_token", n=1, L=32, S=0, K=8, d=128, Hq=2, Hkv=2, B=1, dtype="bf16"),
+    dict(name="mfma_keep_all", n=8 + 5 * 64 + 17, L=64, S=8, K=64, d=128, Hq=2, Hkv=1, B=1, dtype="bf16"),
+    dict(name="mfma_group_of_3", n=3 + 6 * 48 + 5, L=48, S=3, K=12, d=128, Hq=6, Hkv=2, B=1, dtype="bf16"),
+    dict(name="mfma_group_of_8_xcd_map", n=16 + 5 * 64 + 20, L=64, S=16, K=16, d=128, Hq=64, Hkv=8, B=1, dtype="bf16"),
+    dict(name="mfma_chunk_past_one_key_tile", n=32 + 4 * 320 + 100, L=320, S=32, K=80, d=128, Hq=4, Hkv=1, B=2, dtype="bf16"),
 ]
 
 
