@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--kv-copies", type=int, default=4, help="distinct K/V copies rotated over the steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-score-select", action="store_true",
+                    help="call lrsa_score and lrsa_select (two launches) instead of lrsa_score_select (one)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, run one plain 1 GiB device copy (a kernel of known traffic "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -116,8 +118,11 @@ def main():
 
     def step(i):
         K, V = Ks[i % len(Ks)], Vs[i % len(Vs)]
-        lrsa.lrsa_score(p, K, V, score, ws)
-        lrsa.lrsa_select(p, score, idx, ws)
+        if args.separate_score_select:
+            lrsa.lrsa_score(p, K, V, score, ws)
+            lrsa.lrsa_select(p, score, idx, ws)
+        else:
+            lrsa.lrsa_score_select(p, K, V, score, idx, ws)
         lrsa.lrsa_attn_fwd(p, Q, K, V, idx, O, lse, ws)
         lrsa.lrsa_attn_bwd(p, Q, K, V, O, dO, lse, idx, dQ, dK, dV, ws)
 
@@ -166,7 +171,7 @@ def main():
         return sum(kern_ms.get(k, 0.0) * launches.get(k, 0.0) for k in names)
     esz = 2 if w.dtype == "bf16" else 4
     score_bytes = 2 * w.B * w.Hkv * w.n * w.d * esz + 4 * w.B * w.Hkv * Ns * w.L
-    ms_score = stage(["k_score_fused", "k_minmaxT", "k_sigmaT", "k_softmax"])
+    ms_score = stage(["k_score_select_fused", "k_score_fused", "k_minmaxT", "k_sigmaT", "k_softmax"])
     ms_select = stage(["k_select"])
     ms_fwd = stage(["k_fwd_mfma", "k_fwd_genericT"])
     ms_bwd = stage(["k_bwd_rowdot", "k_bwd_dq", "k_bwd_dkv", "k_bwd_dkv_reduce", "k_bwd_dq_genericT", "k_bwd_dkv_genericT"])
@@ -179,7 +184,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B{w.B} Hq{w.Hq} Hkv{w.Hkv} d{w.d} n{w.n} L{w.L} K{w.K} S{w.S} {w.dtype}, {w.structure}",
-                   "pairs_per_head": pairs, "kv_copies": len(Ks)},
+                   "pairs_per_head": pairs, "kv_copies": len(Ks),
+                   "score_select": "lrsa_score + lrsa_select" if args.separate_score_select else "lrsa_score_select (one launch)"},
         "tokens_per_s": w.B * w.n / (ms_per_step * 1e-3),
         "attn_fwd_bwd_tflops_kernels_only": flops_step / max((ms_fwd + ms_bwd) * 1e-3, 1e-12) / 1e12,
         "stages_ms": {"score": ms_score, "select": ms_select, "attn_fwd": ms_fwd, "attn_bwd": ms_bwd},

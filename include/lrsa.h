@@ -101,6 +101,14 @@ int lrsa_score(const lrsa_params *p, const void *K, const void *V, float *score,
 int lrsa_select(const lrsa_params *p, const float *score, int32_t *idx,
                 void *ws, size_t ws_bytes, void *stream);
 
+/* lrsa_score followed by lrsa_select in one call, and in one launch where the chunk fits the fused
+ * kernel: the workgroup that has just scored a chunk (Eq. 4-8) takes its top K while the scores are
+ * still in LDS (text after Eq. 8).  Writes exactly what the two calls would write: score and idx are
+ * bit-identical to theirs.  Arguments as in lrsa_score and lrsa_select; the workspace is the one of
+ * lrsa_score (LRSA_WS_SCORE).  Ns == 0 is legal: nothing is written. */
+int lrsa_score_select(const lrsa_params *p, const void *K, const void *V, float *score, int32_t *idx,
+                      void *ws, size_t ws_bytes, void *stream);
+
 /* Attention forward, Eq. 2-3 under the chunked mask: O[t] = sum_u softmax_u(scale q_t.k_u) v_u over
  * the keys u <= t that are in the sink, in the local window of t's chunk, or listed in idx;
  * lse[t] = log sum_u exp(scale q_t.k_u).  Query head hq reads KV head hq / G.

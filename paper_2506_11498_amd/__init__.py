@@ -4,5 +4,5 @@ the C ABI of include/lrsa.h.  This package holds the kernels' sources (csrc/), t
 and a ctypes binding; `inputs` is the seeded synthetic-input generator."""
 from . import inputs  # noqa: F401
 from .binding import (IMPL_AUTO, IMPL_GENERIC, LrsaError, LrsaParams, lib, lrsa_attn_bwd, lrsa_attn_fwd,  # noqa: F401
-                      lrsa_score, lrsa_select, make_params, num_scored_chunks, params_for, timing_enable,
+                      lrsa_score, lrsa_score_select, lrsa_select, make_params, num_scored_chunks, params_for, timing_enable,
                       timing_records, workspace_bytes)

@@ -21,7 +21,7 @@ IMPL_AUTO, IMPL_GENERIC = 0, 1
 WS_SCORE, WS_SELECT, WS_ATTN_FWD, WS_ATTN_BWD = 0, 1, 2, 3
 
 EXPORTS = ("lrsa_abi_version", "lrsa_last_error", "lrsa_num_scored_chunks", "lrsa_workspace_bytes",
-           "lrsa_score", "lrsa_select", "lrsa_attn_fwd", "lrsa_attn_bwd",
+           "lrsa_score", "lrsa_select", "lrsa_score_select", "lrsa_attn_fwd", "lrsa_attn_bwd",
            "lrsa_timing_enable", "lrsa_timing_count", "lrsa_timing_read")
 
 
@@ -61,6 +61,7 @@ def lib() -> ctypes.CDLL:
         vp, sz = ctypes.c_void_p, ctypes.c_size_t
         L.lrsa_score.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.lrsa_select.argtypes = [vp, vp, vp, vp, sz, vp]
+        L.lrsa_score_select.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
         L.lrsa_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.lrsa_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         _lib = L
@@ -141,6 +142,19 @@ def lrsa_select(p: LrsaParams, score: torch.Tensor, idx: Optional[torch.Tensor] 
     ws, nb = _workspace(p, WS_SELECT, score.device, ws)
     _check(lib().lrsa_select(ctypes.byref(p), _ptr(score), _ptr(idx), _ptr(ws), nb, _stream()))
     return idx
+
+
+def lrsa_score_select(p: LrsaParams, K: torch.Tensor, V: torch.Tensor, score: Optional[torch.Tensor] = None,
+                      idx: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """lrsa_score and lrsa_select in one call (one launch where the fused kernel applies): (score, idx)."""
+    Ns = num_scored_chunks(p)
+    if score is None:
+        score = torch.empty((p.batch, p.heads_kv, Ns, p.lag), dtype=torch.float32, device=K.device)
+    if idx is None:
+        idx = torch.empty((p.batch, p.heads_kv, Ns, p.topk), dtype=torch.int32, device=K.device)
+    ws, nb = _workspace(p, WS_SCORE, K.device, ws)
+    _check(lib().lrsa_score_select(ctypes.byref(p), _ptr(K), _ptr(V), _ptr(score), _ptr(idx), _ptr(ws), nb, _stream()))
+    return score, idx
 
 
 def lrsa_attn_fwd(p: LrsaParams, Q, K, V, idx, O: Optional[torch.Tensor] = None,

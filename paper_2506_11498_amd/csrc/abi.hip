@@ -137,6 +137,20 @@ int lrsa_select(const lrsa_params* p, const float* score, int32_t* idx, void* ws
     return hip_result(lrsa::launch_select(D, score, idx, ws, (hipStream_t)stream), "lrsa_select");
 }
 
+int lrsa_score_select(const lrsa_params* p, const void* K, const void* V, float* score, int32_t* idx, void* ws,
+                      size_t ws_bytes, void* stream) {
+    lrsa::Dims D;
+    int rc = make_dims(p, &D);
+    if (rc != LRSA_OK) return rc;
+    if (D.Ns == 0) return LRSA_OK;
+    if (!K || !V || !score || !idx)
+        return fail(LRSA_ERR_INVALID_ARG, "lrsa_score_select: K, V, score and idx must not be NULL");
+    if (misaligned16(K) || misaligned16(V))
+        return fail(LRSA_ERR_INVALID_ARG, "lrsa_score_select: K and V must be 16-byte aligned");
+    if ((rc = check_ws(p, D, LRSA_WS_SCORE, ws, ws_bytes)) != LRSA_OK) return rc;
+    return hip_result(lrsa::launch_score_select(D, K, V, score, idx, ws, (hipStream_t)stream), "lrsa_score_select");
+}
+
 int lrsa_attn_fwd(const lrsa_params* p, const void* Q, const void* K, const void* V, const int32_t* idx, void* O,
                   float* lse, void* ws, size_t ws_bytes, void* stream) {
     lrsa::Dims D;

@@ -35,6 +35,7 @@ hipError_t launch_score(const Dims&, const void* K, const void* V, float* score,
 
 size_t select_ws_bytes(const Dims&);
 hipError_t launch_select(const Dims&, const float* score, int32_t* idx, void* ws, hipStream_t st);
+hipError_t launch_score_select(const Dims&, const void* K, const void* V, float* score, int32_t* idx, void* ws, hipStream_t st);
 
 size_t attn_fwd_generic_ws_bytes(const Dims&);
 hipError_t launch_attn_fwd_generic(const Dims&, const void* Q, const void* K, const void* V, const int32_t* idx,

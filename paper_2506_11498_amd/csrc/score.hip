@@ -7,7 +7,7 @@
 // All arithmetic is fp32 on the stored values with IEEE division and square root, two-pass
 // variance, max-subtracted softmax.  Rows are read with 16-byte loads, a row being spread over
 // consecutive lanes so that a wave reads whole rows back to back.
-#include "common.h"
+#include "select_block.h"
 
 namespace lrsa {
 
@@ -178,10 +178,11 @@ __global__ __launch_bounds__(SCORE_THREADS) void k_softmax(Dims D, const float* 
 constexpr int FUSED_THREADS = 1024;
 constexpr int FUSED_MAX_L = 4096;
 
-template <typename T>
+// SELECT: the workgroup also takes the top K of the chunk it has just scored (the scores are still in LDS).
+template <typename T, bool SELECT>
 __global__ __launch_bounds__(FUSED_THREADS) void k_score_fused(Dims D, const T* __restrict__ Kp,
                                                                const T* __restrict__ Vp,
-                                                               float* __restrict__ score) {
+                                                               float* __restrict__ score, int32_t* __restrict__ idx) {
     constexpr int VEC = Elem<T>::VEC;
     constexpr int NW = FUSED_THREADS / 64;
     const int lpr = D.d / VEC;                // lanes per row
@@ -326,14 +327,30 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_score_fused(Dims D, const T* 
     zk = block_red(zk, false);
     zv = block_red(zv, false);
     float* out = score + (int64_t(bh) * D.Ns + p) * D.L;
-    for (int r = tid; r < D.L; r += FUSED_THREADS) out[r] = expf(sig[0][r] - mk) / zk + expf(sig[1][r] - mv) / zv;
+    for (int r = tid; r < D.L; r += FUSED_THREADS) {
+        const float sc = expf(sig[0][r] - mk) / zk + expf(sig[1][r] - mv) / zv;
+        out[r] = sc;
+        if (SELECT) sig[0][r] = sc;     // each thread overwrites only what it alone has read
+    }
+    if (SELECT) {
+        __shared__ SelectLds sel;
+        __syncthreads();
+        select_topk_block<FUSED_THREADS>(reinterpret_cast<const uint32_t*>(sig[0]), D.L, D.K, D.S + p * D.L,
+                                         idx + (int64_t(bh) * D.Ns + p) * D.K, sel);
+    }
 }
 
+// idx != nullptr: scores AND the selection (one launch when the fused kernel applies, else two)
 template <typename T>
-static hipError_t run_score(const Dims& D, const void* K, const void* V, float* score, void* ws, hipStream_t st) {
+static hipError_t run_score(const Dims& D, const void* K, const void* V, float* score, int32_t* idx, void* ws,
+                            hipStream_t st) {
     if (D.L <= FUSED_MAX_L) {
-        LRSA_TIMED_LAUNCH("k_score_fused", st, k_score_fused<T>, dim3(D.Ns, D.B * D.Hkv), dim3(FUSED_THREADS), 0, st, D,
-                          (const T*)K, (const T*)V, score);
+        if (idx)
+            LRSA_TIMED_LAUNCH("k_score_select_fused", st, (k_score_fused<T, true>), dim3(D.Ns, D.B * D.Hkv), dim3(FUSED_THREADS),
+                              0, st, D, (const T*)K, (const T*)V, score, idx);
+        else
+            LRSA_TIMED_LAUNCH("k_score_fused", st, (k_score_fused<T, false>), dim3(D.Ns, D.B * D.Hkv), dim3(FUSED_THREADS), 0,
+                              st, D, (const T*)K, (const T*)V, score, idx);
         return hipGetLastError();
     }
     float* mm = reinterpret_cast<float*>(ws);
@@ -342,12 +359,20 @@ static hipError_t run_score(const Dims& D, const void* K, const void* V, float* 
     LRSA_TIMED_LAUNCH("k_minmaxT", st, k_minmax<T>, grid, dim3(SCORE_THREADS), 0, st, D, (const T*)K, (const T*)V, mm);
     LRSA_TIMED_LAUNCH("k_sigmaT", st, k_sigma<T>, grid, dim3(SCORE_THREADS), 0, st, D, (const T*)K, (const T*)V, mm, sigma);
     LRSA_TIMED_LAUNCH("k_softmax", st, k_softmax, dim3(D.Ns, D.B * D.Hkv), dim3(SCORE_THREADS), 0, st, D, sigma, score);
-    return hipGetLastError();
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && idx) e = launch_select(D, score, idx, nullptr, st);
+    return e;
 }
 
 hipError_t launch_score(const Dims& D, const void* K, const void* V, float* score, void* ws, hipStream_t st) {
     if (D.Ns == 0) return hipSuccess;
-    return D.dtype == 0 ? run_score<float>(D, K, V, score, ws, st) : run_score<bf16_t>(D, K, V, score, ws, st);
+    return D.dtype == 1 ? run_score<bf16_t>(D, K, V, score, nullptr, ws, st) : run_score<float>(D, K, V, score, nullptr, ws, st);
+}
+
+hipError_t launch_score_select(const Dims& D, const void* K, const void* V, float* score, int32_t* idx, void* ws,
+                               hipStream_t st) {
+    if (D.Ns == 0) return hipSuccess;
+    return D.dtype == 1 ? run_score<bf16_t>(D, K, V, score, idx, ws, st) : run_score<float>(D, K, V, score, idx, ws, st);
 }
 
 }  // namespace lrsa

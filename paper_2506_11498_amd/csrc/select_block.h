@@ -1,0 +1,105 @@
+// Top-K of one lag window inside one workgroup (text after Eq. 8 of the paper): the K positions with the
+// largest score, ties to the lowest position, written ascending.
+//
+// Scores are positive floats, so their bit patterns order like unsigned integers.  The workgroup finds
+// the bit pattern of the K-th largest score with a 4-pass, 8-bit radix select (histogram in LDS, suffix
+// scan over the 256 buckets), then compacts in position order: every score above the threshold, plus the
+// first `need` scores equal to it.  All integer work, hence deterministic.  Used by the stand-alone
+// selection kernel (keys in global memory) and by the fused scoring kernel (keys in LDS).
+#pragma once
+#include "common.h"
+
+namespace lrsa {
+
+struct SelectLds {
+    int hist[256];
+    int sm[16];
+    uint32_t prefix;
+    int need;
+};
+
+// exclusive prefix sum of `v` over the NT threads of the block; *total receives the block sum
+template <int NT>
+__device__ __forceinline__ int block_exscan(int v, int* sm /*[NT/64]*/, int* total) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int t = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += t;
+    }
+    __syncthreads();
+    if (lane == 63) sm[w] = inc;
+    __syncthreads();
+    int off = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < NT / 64; ++i) {
+        const int s = sm[i];
+        if (i < w) off += s;
+        tot += s;
+    }
+    *total = tot;
+    return off + inc - v;
+}
+
+// key: L bit patterns (global or LDS); out: K positions base + r, ascending.  Every thread of the block calls.
+template <int NT>
+__device__ __forceinline__ void select_topk_block(const uint32_t* key, int L, int K, int base, int32_t* out,
+                                                  SelectLds& sh) {
+    static_assert(NT >= 256 && NT % 64 == 0 && NT <= 1024, "block size");
+    const int tid = threadIdx.x, lane = tid & 63;
+    uint32_t prefix = 0, mask = 0;
+    int need = K;  // how many of the elements matching `prefix` on the decided bytes are still wanted
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) sh.hist[tid] = 0;
+        __syncthreads();
+        for (int r = tid; r < L; r += NT) {
+            const uint32_t k = key[r];
+            if ((k & mask) == prefix) atomicAdd(&sh.hist[(k >> shift) & 255], 1);
+        }
+        __syncthreads();
+        // the first wave walks the buckets from the top: lane l owns buckets 255-4l .. 252-4l, an exclusive
+        // scan over the lanes counts the elements in higher buckets
+        if (tid < 64) {
+            int c[4], tot = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { c[i] = sh.hist[255 - 4 * lane - i]; tot += c[i]; }
+            int inc = tot;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(inc, o, 64);
+                if (lane >= o) inc += t;
+            }
+            int above = inc - tot;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (above < need && need <= above + c[i]) {
+                    sh.prefix = prefix | (uint32_t(255 - 4 * lane - i) << shift);
+                    sh.need = need - above;
+                }
+                above += c[i];
+            }
+        }
+        __syncthreads();
+        prefix = sh.prefix;
+        need = sh.need;
+        mask |= 0xffu << shift;
+    }
+    // prefix is now the K-th largest bit pattern; `need` of the elements equal to it are taken.  One packed
+    // scan per NT elements: larger ones in the low half-word, equal ones in the high half-word.
+    int gt_seen = 0, eq_seen = 0;
+    for (int r0 = 0; r0 < L; r0 += NT) {
+        const int r = r0 + tid;
+        const uint32_t k = r < L ? key[r] : 0u;
+        const int is_gt = (r < L && k > prefix) ? 1 : 0;
+        const int is_eq = (r < L && k == prefix) ? 1 : 0;
+        int total;
+        const int before = block_exscan<NT>(is_gt | (is_eq << 16), sh.sm, &total);
+        const int gt_before = gt_seen + (before & 0xffff), eq_before = eq_seen + (before >> 16);
+        if (is_gt || (is_eq && eq_before < need)) out[gt_before + min(eq_before, need)] = base + r;
+        gt_seen += total & 0xffff;
+        eq_seen += total >> 16;
+    }
+}
+
+}  // namespace lrsa

@@ -154,6 +154,28 @@ def test_select_is_exact_on_heavily_tied_scores():
     assert np.array_equal(got, ref.select(sc, w.S, w.L, w.K))
 
 
+@pytest.mark.parametrize("cfg", [
+    dict(n=3 + 9 * 300 + 5, L=300, S=3, K=77, d=64, Hq=2, Hkv=2, B=2, dtype="f32"),           # ragged L, fp32
+    dict(n=16 + 6 * 1024 + 100, L=1024, S=16, K=256, d=128, Hq=2, Hkv=2, B=1, dtype="bf16"),   # one key per thread
+    dict(n=8 + 4 * 4096 + 9, L=4096, S=8, K=1000, d=128, Hq=1, Hkv=1, B=1, dtype="bf16"),     # largest fused chunk
+    dict(n=8 + 3 * 4100 + 9, L=4100, S=8, K=17, d=128, Hq=1, Hkv=1, B=1, dtype="bf16"),       # beyond it: two launches
+    dict(n=40, L=32, S=64, K=8, d=128, Hq=1, Hkv=1, B=1, dtype="bf16"),                       # nothing to score
+], ids=["f32_ragged", "bf16_L1024", "bf16_L4096", "bf16_L4100_fallback", "no_chunks"])
+def test_fused_score_select_equals_the_two_calls_and_the_oracle(cfg):
+    w = inputs.small_workload(**cfg)
+    x = inputs.make_inputs(w)
+    xd = {k: v.to(DEV) for k, v in x.items()}
+    p, score, idx = run_score_select(w, xd)
+    score_f, idx_f = lrsa.lrsa_score_select(p, xd["K"], xd["V"])
+    assert torch.equal(score_f, score) and torch.equal(idx_f, idx)      # bit-identical to the two calls
+    if lrsa.num_scored_chunks(p):
+        xf = {k: v.float().numpy() for k, v in x.items()}
+        sc_ref = ref.score(xf["K"], xf["V"], w.S, w.L)
+        idx_ref = ref.select(sc_ref, w.S, w.L, w.K)
+        assert np.allclose(to_np(score_f), sc_ref, rtol=2e-5, atol=1e-9)
+        check_selection_in_tie_window(w, idx_f.cpu().numpy(), idx_ref, sc_ref)
+
+
 def test_strided_views_and_preallocated_outputs():
     """Q/K/V given as [B, n, H, d] storage viewed as [B, H, n, d] (position stride = H*d)."""
     w = inputs.small_workload(n=8 + 5 * 32 + 3, L=32, S=8, K=8, d=128, Hq=4, Hkv=2, B=2, dtype="bf16")
