@@ -65,6 +65,9 @@ WORKLOADS: Dict[str, Workload] = {
     "C3": Workload("C3", 1, 32, 32, 128, 16384, 512, 128, 16, "bf16", 1003, "channel_scale"),
     "C4": Workload("C4", 1, 32, 8, 128, 32768, 1024, 256, 64, "bf16", 1004, "mean_drift"),
     "C5": Workload("C5", 1, 64, 8, 128, 131072, 2048, 512, 64, "bf16", 1005, "heavy_tokens"),
+    # the paper's own fine-tuning shape (Experiment Setup): 32K tokens, lag 1024, retention r = 0.5, on the
+    # head geometry of the 1.5B model it trains (12 query heads, 2 KV heads, head_dim 128); sink as in C4
+    "C6": Workload("C6", 1, 12, 2, 128, 32768, 1024, 512, 64, "bf16", 1006, "mean_drift"),
 }
 
 

@@ -271,5 +271,9 @@ def test_workload_C4_gqa_32k():
     full_workload_parity("C4", kv_heads=[3], n_rows=192, n_cols=32)
 
 
+def test_workload_C6_paper_training_shape():
+    full_workload_parity("C6", kv_heads=[1], n_rows=160, n_cols=32)
+
+
 def test_workload_C5_stress_128k():
     full_workload_parity("C5", kv_heads=[6], n_rows=96, n_cols=12, late_cols_only=True)
