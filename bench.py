@@ -42,7 +42,7 @@ def pair_counts(w, local_prev=1):
     return int((gathered + window).sum()), int(gathered.sum())
 
 
-def cpu_baseline(w, x, chunks=16):
+def cpu_baseline(w, x, chunks=24):
     """Time the oracle, as it stands, on a bounded sample: fp32 scores and selection of every head
     (NumPy), then the whole forward and backward (every query row: O, lse, D, dQ; every key column:
     dK, dV) of the first S + chunks*L tokens of ONE KV group in the fp64 C code with OpenMP.  The

@@ -3,18 +3,18 @@
 // D = rowsum(dO * O), dS = A * (dA - D), dQ = scale dS K, dK = scale dS^T Q.
 //
 // Deterministic, no atomics.  Four launches on one stream:
-//   k_bwd_rowdot   D[b,hq,t] = dO[t] . O[t], and lse in log2 units
-//   k_bwd_dq       query-outer: a workgroup owns 128 queries and walks their key stream exactly
-//                  like the forward (gather list, then the local window), recomputing A
-//   k_bwd_dkv      key-outer, mode GATHER: a workgroup owns 128 consecutive entries of one KV
-//                  head's gather list (sink ++ survivors) and a range of query chunks; it writes
-//                  fp32 partial dK, dV rows for those entries into the workspace
-//   k_bwd_dkv      key-outer, mode WINDOW: a workgroup owns 128 consecutive positions and walks
-//                  the queries that see them through the local window (own chunk causally, the
-//                  next local_prev chunks in full); its epilogue adds the GATHER partials of the
-//                  positions that are sink tokens or survivors, scales and writes dK, dV.
-// In the key-outer kernel a lane owns one key column of S = Q K^T, so K and V fragments stay in
-// registers for the whole walk; Q and dO rows stream through LDS 32 rows at a time and are read
+//   k_bwd_rowdot      D[b,hq,t] = dO[t] . O[t], and lse in log2 units
+//   k_bwd_dq          query-outer: a workgroup owns 256 (head, query) rows of one KV group and walks their
+//                     key stream exactly like the forward (gather list, then the local window), recomputing A
+//   k_bwd_dkv         key-outer, two kinds of workgroups in one launch.  GATHER: 256 consecutive entries of one
+//                     KV head's gather list (sink ++ survivors) x one slice of query chunks -> fp32 partial
+//                     dK, dV rows in the workspace.  WINDOW: 256 consecutive positions x the queries that see
+//                     them through the local window (own chunk causally, the next local_prev chunks in full);
+//                     positions outside the gather list are written as final dK, dV, listed ones as one more
+//                     fp32 partial.
+//   k_bwd_dkv_reduce  listed positions: window partial + the slices, in a fixed order -> dK, dV
+// In the key-outer kernel a lane owns one key column of S = Q K^T: K fragments stay in registers for the
+// whole walk, the workgroup's V rows in LDS; Q and dO rows stream through LDS 64 rows at a time and are read
 // both row-wise (for S and dA) and transposed (for dV^T += dO^T A and dK^T += Q^T dS).
 #include "mfma_tiles.h"
 

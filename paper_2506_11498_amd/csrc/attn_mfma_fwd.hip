@@ -7,7 +7,7 @@
 // contiguous local window up to the query itself.  Stream entry j is visible to query t iff
 // j <= ng + t - cs, so only the last tiles need a mask.  The stream is walked in tiles of 64
 // keys; K and V rows of a tile are copied (gathered by position) asynchronously from global
-// memory straight into a two-stage LDS ring, one tile ahead, row-major and swizzled.
+// memory straight into a four-stage LDS ring, three tiles ahead, row-major and swizzled.
 //
 // Per tile and wave:  S^T = K Q^T  (keys x queries, so a lane owns one query column and the
 // softmax statistics are per lane), P^T = exp2(S^T - m), O^T += V^T P^T with the accumulator

@@ -1,10 +1,14 @@
 // LagKV scoring kernels (Eq. 4-8 of the paper) for gfx950.
 //
-// Three launches on one stream:
-//   k_minmax   per-channel min / max over a slice of the rows of the reference chunk p+1 (Eq. 4-5)
-//   k_sigma    rows of chunk p normalised by the combined min / max (Eq. 6), Std over channels
-//   k_softmax  Softmax over the L tokens of the chunk for K and for V, summed (Eq. 7-8)
-// All arithmetic is fp32 on the stored values with IEEE division and square root, two-pass
+// Chunks of up to 4096 tokens: ONE launch, k_score_fused, one workgroup of 1024 threads per (batch, KV head,
+// chunk p): per-channel min / max over the rows of the reference chunk p+1 (Eq. 4-5), rows of chunk p
+// normalised by them (Eq. 6) and their standard deviation over the channels, then the softmax over the
+// chunk's tokens for K and for V, summed (Eq. 7-8); optionally the top-K selection of the chunk right away.
+// Longer chunks: three launches through the workspace,
+//   k_minmax   per-channel min / max over a slice of the rows of the reference chunk p+1
+//   k_sigma    rows of chunk p normalised by the combined min / max, Std over channels
+//   k_softmax  Softmax over the L tokens of the chunk for K and for V, summed
+// All arithmetic is fp32 on the stored values with correctly rounded division and square root, two-pass
 // variance, max-subtracted softmax.  Rows are read with 16-byte loads, a row being spread over
 // consecutive lanes so that a wave reads whole rows back to back.
 #include "select_block.h"
