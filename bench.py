@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--kv-copies", type=int, default=4, help="distinct K/V copies rotated over the steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--impl", choices=["auto", "compact"], default="auto",
+                    help="compact: attention over a physically condensed KV cache (LRSA_IMPL_COMPACT)")
     ap.add_argument("--separate-score-select", action="store_true",
                     help="call lrsa_score and lrsa_select (two launches) instead of lrsa_score_select (one)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -106,7 +108,8 @@ def main():
     Q, dO = x["Q"].to(dev), x["dO"].to(dev)
     Ks = [x["K"].to(dev) for _ in range(max(args.kv_copies, 1))]
     Vs = [x["V"].to(dev) for _ in range(max(args.kv_copies, 1))]
-    p = lrsa.params_for(Q, Ks[0], sink=w.S, lag=w.L, topk=w.K)
+    p = lrsa.params_for(Q, Ks[0], sink=w.S, lag=w.L, topk=w.K,
+                        impl=lrsa.IMPL_COMPACT if args.impl == "compact" else lrsa.IMPL_AUTO)
     Ns = lrsa.num_scored_chunks(p)
     score = torch.empty((w.B, w.Hkv, Ns, w.L), dtype=torch.float32, device=dev)
     idx = torch.empty((w.B, w.Hkv, Ns, w.K), dtype=torch.int32, device=dev)
@@ -173,8 +176,9 @@ def main():
     score_bytes = 2 * w.B * w.Hkv * w.n * w.d * esz + 4 * w.B * w.Hkv * Ns * w.L
     ms_score = stage(["k_score_select_fused", "k_score_fused", "k_minmaxT", "k_sigmaT", "k_softmax"])
     ms_select = stage(["k_select"])
-    ms_fwd = stage(["k_fwd_mfma", "k_fwd_genericT"])
-    ms_bwd = stage(["k_bwd_rowdot", "k_bwd_dq", "k_bwd_dkv", "k_bwd_dkv_reduce", "k_bwd_dq_genericT", "k_bwd_dkv_genericT"])
+    ms_fwd = stage(["k_fwd_mfma", "k_fwd_genericT"])      # k_compact_kv runs in both calls: counted below
+    ms_bwd = stage(["k_bwd_rowdot", "k_bwd_dq", "k_bwd_dkv", "k_bwd_dkv_reduce", "k_bwd_dq_genericT", "k_bwd_dkv_genericT",
+                    "k_compact_kv"])
     ss_bytes = score_bytes + 4 * w.B * w.Hkv * Ns * w.K     # K and V read once, scores and idx written once
     ss_gbps = ss_bytes / max(ms_score + ms_select, 1e-9) / 1e6
     out = {
@@ -185,6 +189,7 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B{w.B} Hq{w.Hq} Hkv{w.Hkv} d{w.d} n{w.n} L{w.L} K{w.K} S{w.S} {w.dtype}, {w.structure}",
                    "pairs_per_head": pairs, "kv_copies": len(Ks),
+                   "impl": args.impl,
                    "score_select": "lrsa_score + lrsa_select" if args.separate_score_select else "lrsa_score_select (one launch)"},
         "tokens_per_s": w.B * w.n / (ms_per_step * 1e-3),
         # context only: the flops of DENSE causal attention over the same step time (what sparse-attention

@@ -48,8 +48,13 @@ typedef enum { LRSA_F32 = 0, LRSA_BF16 = 1 } lrsa_dtype;
 
 /* Which kernels serve the attention calls. */
 typedef enum {
-    LRSA_IMPL_AUTO = 0,   /* bf16 with head_dim 128: MFMA kernels; everything else: generic kernels */
-    LRSA_IMPL_GENERIC = 1 /* force the plain fp32-arithmetic kernels (any supported dtype/head_dim)  */
+    LRSA_IMPL_AUTO = 0,    /* bf16 with head_dim 128: MFMA kernels; everything else: generic kernels */
+    LRSA_IMPL_GENERIC = 1, /* force the plain fp32-arithmetic kernels (any supported dtype/head_dim)  */
+    LRSA_IMPL_COMPACT = 2  /* MFMA kernels over a physically condensed KV cache: lrsa_attn_fwd and
+                              lrsa_attn_bwd first copy the rows of the gather list (sink, survivors) into
+                              a contiguous buffer in the workspace and read that instead of gathering by
+                              index in their loops; same results bit for bit, a larger workspace.  Where
+                              the MFMA kernels do not apply it behaves like LRSA_IMPL_AUTO.            */
 } lrsa_impl;
 
 typedef struct {

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("LRSA_LIB", os.path.join(_HERE, "liblrsa.so"))
 
 LRSA_F32, LRSA_BF16 = 0, 1
-IMPL_AUTO, IMPL_GENERIC = 0, 1
+IMPL_AUTO, IMPL_GENERIC, IMPL_COMPACT = 0, 1, 2
 WS_SCORE, WS_SELECT, WS_ATTN_FWD, WS_ATTN_BWD = 0, 1, 2, 3
 
 EXPORTS = ("lrsa_abi_version", "lrsa_last_error", "lrsa_num_scored_chunks", "lrsa_workspace_bytes",

@@ -36,7 +36,8 @@ int make_dims(const lrsa_params* p, lrsa::Dims* D) {
     if (p->dtype != LRSA_F32 && p->dtype != LRSA_BF16) return fail(LRSA_ERR_UNSUPPORTED, "dtype %d is not built", p->dtype);
     if (p->head_dim != 64 && p->head_dim != 128)
         return fail(LRSA_ERR_UNSUPPORTED, "head_dim %d is not built (64 and 128 are)", p->head_dim);
-    if (p->impl != LRSA_IMPL_AUTO && p->impl != LRSA_IMPL_GENERIC) return fail(LRSA_ERR_INVALID_ARG, "unknown impl %d", p->impl);
+    if (p->impl != LRSA_IMPL_AUTO && p->impl != LRSA_IMPL_GENERIC && p->impl != LRSA_IMPL_COMPACT)
+        return fail(LRSA_ERR_INVALID_ARG, "unknown impl %d", p->impl);
     if (!(p->softmax_scale == p->softmax_scale) || std::isinf(p->softmax_scale))
         return fail(LRSA_ERR_INVALID_ARG, "softmax_scale is not finite");
     const int vec = p->dtype == LRSA_F32 ? 4 : 8;  // elements per 16 bytes
@@ -61,13 +62,14 @@ int make_dims(const lrsa_params* p, lrsa::Dims* D) {
     D->Ns = D->nq - 1 - D->lp > 0 ? D->nq - 1 - D->lp : 0;
     D->scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / std::sqrt((float)p->head_dim);
     D->dtype = p->dtype;
+    D->compact = p->impl == LRSA_IMPL_COMPACT ? 1 : 0;
     for (int i = 0; i < 3; ++i) { D->qs[i] = p->q_stride[i]; D->ks[i] = p->kv_stride[i]; }
     if (p->batch * (int64_t)p->heads_kv * 2 > 65535 || p->heads_q > 65535 || D->Ns > 65535)
         return fail(LRSA_ERR_UNSUPPORTED, "batch*heads or chunk count beyond the launch grid limits");
     return LRSA_OK;
 }
 
-bool use_mfma(const lrsa_params* p, const lrsa::Dims& D) { return p->impl == LRSA_IMPL_AUTO && lrsa::mfma_supported(D); }
+bool use_mfma(const lrsa_params* p, const lrsa::Dims& D) { return p->impl != LRSA_IMPL_GENERIC && lrsa::mfma_supported(D); }
 
 size_t ws_need(const lrsa_params* p, const lrsa::Dims& D, int which) {
     switch (which) {

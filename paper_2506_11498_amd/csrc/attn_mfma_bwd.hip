@@ -45,7 +45,7 @@ struct BwdPlan {
     int gl_total, gtiles;       // gather list length per KV head, its tiles of 128
     int qch, nsl;               // query chunks per slice, slices per gather tile (<= KV_MAX_SLICES)
     int gather_wgs;             // workgroups of the GATHER part of the dK/dV launch (a multiple of 8)
-    size_t off_lse2, off_part, bytes;   // workspace: D, lse in log2 units, then the fp32 partials
+    size_t off_lse2, off_part, off_compact, bytes;   // workspace: D, lse in log2 units, the fp32 partials, condensed K/V
 };
 
 static BwdPlan make_plan(const Dims& D) {
@@ -68,7 +68,8 @@ static BwdPlan make_plan(const Dims& D) {
     P.gather_wgs = P.gtiles > 0 ? (D.B * D.Hkv * P.nsl + 7) / 8 * 8 * P.gtiles : 0;
     // slots 0 .. nsl-1: the GATHER workgroups' slices; slot nsl: what the WINDOW workgroups add to listed positions
     const size_t part = size_t(2) * (P.nsl + 1) * D.B * D.Hkv * P.gl_total * 128 * 4;
-    P.bytes = P.off_part + align256(part);
+    P.off_compact = P.off_part + align256(part);
+    P.bytes = P.off_compact + compact_kv_bytes(D);
     return P;
 }
 
@@ -158,7 +159,8 @@ __device__ __forceinline__ void dq_tile(const unsigned char* sK, const unsigned 
 }
 
 // GH query heads of one KV group share the workgroup (8 waves = GH heads x 256/GH queries), as in the forward.
-template <int GH>
+// COMPACT: the rows of the gather list come from the condensed cache Kc, Vc (contiguous), no index is read.
+template <int GH, bool COMPACT>
 __global__ __launch_bounds__(DQ_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t* __restrict__ Q,
                                                            const bf16_t* __restrict__ K,
                                                            const bf16_t* __restrict__ V,
@@ -166,6 +168,8 @@ __global__ __launch_bounds__(DQ_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t* 
                                                            const float* __restrict__ lse,
                                                            const float* __restrict__ Dsum,
                                                            const int32_t* __restrict__ idx,
+                                                           const bf16_t* __restrict__ Kc,
+                                                           const bf16_t* __restrict__ Vc,
                                                            bf16_t* __restrict__ dQ, QTileMap M) {
     constexpr int WPH = DQ_WAVES / GH;   // waves per head
     constexpr int QT = 32 * WPH;         // queries per head and workgroup
@@ -216,21 +220,31 @@ __global__ __launch_bounds__(DQ_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t* 
     const int lim = ng + tq - cs;
     const int wave_lim_max = ng + min(t0 + wq * 32 + 31, t_last) - cs;
 
-    int pos[2];
+    const int64_t coff = COMPACT ? (int64_t(b) * D.Hkv + h) * (int64_t(D.S) + int64_t(D.K) * D.Ns) * 128 : 0;
+    const bf16_t* Kc_h = Kc + coff;
+    const bf16_t* Vc_h = Vc + coff;
+    int pos[2];   // COMPACT: stream entries; else positions (fetched through idx one tile ahead)
     auto fetch_pos = [&](int tile) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const int j = tile * DQ_BN + async_row(8 * wave + 4 * i, lane);
-            pos[i] = stream_pos(D, idx_h, j < m_max ? j : m_max - 1, ng, cs);
+            int j = tile * DQ_BN + async_row(8 * wave + 4 * i, lane);
+            j = j < m_max ? j : m_max - 1;
+            pos[i] = COMPACT ? j : stream_pos(D, idx_h, j, ng, cs);
         }
     };
     auto issue = [&](unsigned char* sK, unsigned char* sV) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int r4 = 8 * wave + 4 * i;
-            const int64_t off = int64_t(pos[i]) * D.ks[2] + async_chunk(async_row(r4, lane), lane) * 8;
-            async_rows4(Kh + off, sK, r4);
-            async_rows4(Vh + off, sV, r4);
+            const int ch = async_chunk(async_row(r4, lane), lane) * 8;
+            if (COMPACT) {
+                async_rows4(stream_row(Kc_h, Kh, D.ks[2], pos[i], ng, cs) + ch, sK, r4);
+                async_rows4(stream_row(Vc_h, Vh, D.ks[2], pos[i], ng, cs) + ch, sV, r4);
+            } else {
+                const int64_t off = int64_t(pos[i]) * D.ks[2] + ch;
+                async_rows4(Kh + off, sK, r4);
+                async_rows4(Vh + off, sV, r4);
+            }
         }
     };
 
@@ -740,14 +754,23 @@ hipError_t launch_attn_bwd_mfma(const Dims& D, const void* Q, const void* K, con
         const int gh = heads_per_wg(D);
         const QTileMap M = make_qtile_map(D, gh, DQ_WAVES);
         const int64_t wgs = int64_t(D.B) * D.Hkv * M.per_unit;
-        if (wgs > 0) {
-            if (gh == 4)
-                LRSA_TIMED_LAUNCH("k_bwd_dq", st, k_bwd_dq<4>, dim3((unsigned)wgs), dim3(DQ_THREADS), 0, st, D, q, k, v, g, lse2, Dsum, idx, (bf16_t*)dQ, M);
-            else if (gh == 2)
-                LRSA_TIMED_LAUNCH("k_bwd_dq", st, k_bwd_dq<2>, dim3((unsigned)wgs), dim3(DQ_THREADS), 0, st, D, q, k, v, g, lse2, Dsum, idx, (bf16_t*)dQ, M);
-            else
-                LRSA_TIMED_LAUNCH("k_bwd_dq", st, k_bwd_dq<1>, dim3((unsigned)wgs), dim3(DQ_THREADS), 0, st, D, q, k, v, g, lse2, Dsum, idx, (bf16_t*)dQ, M);
+        const bool compact = D.compact && P.gl_total > 0;
+        const bf16_t *kc = nullptr, *vc = nullptr;
+        if (compact && wgs > 0) {
+            kc = reinterpret_cast<const bf16_t*>(reinterpret_cast<const char*>(ws) + P.off_compact);
+            vc = reinterpret_cast<const bf16_t*>(reinterpret_cast<const char*>(ws) + P.off_compact + compact_kv_bytes(D) / 2);
+            const hipError_t e = launch_compact_kv(D, K, V, idx, (void*)kc, (void*)vc, st);
+            if (e != hipSuccess) return e;
         }
+#define LRSA_DQ_LAUNCH(GH_, C_)                                                                                     \
+    LRSA_TIMED_LAUNCH("k_bwd_dq", st, (k_bwd_dq<GH_, C_>), dim3((unsigned)wgs), dim3(DQ_THREADS), 0, st, D, q, k, v, g, lse2, \
+                      Dsum, idx, kc, vc, (bf16_t*)dQ, M)
+        if (wgs > 0) {
+            if (gh == 4) { if (compact) LRSA_DQ_LAUNCH(4, true); else LRSA_DQ_LAUNCH(4, false); }
+            else if (gh == 2) { if (compact) LRSA_DQ_LAUNCH(2, true); else LRSA_DQ_LAUNCH(2, false); }
+            else { if (compact) LRSA_DQ_LAUNCH(1, true); else LRSA_DQ_LAUNCH(1, false); }
+        }
+#undef LRSA_DQ_LAUNCH
     }
     const int ktiles = P.sink_tiles_k + D.nq * P.tpc_k;
     const int64_t wgs = int64_t(P.gather_wgs) + int64_t(D.B) * D.Hkv * ktiles;

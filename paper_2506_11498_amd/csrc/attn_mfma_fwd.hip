@@ -22,7 +22,32 @@ constexpr int FWD_WAVES = 8;   // waves per workgroup (two per SIMD), 32 queries
 constexpr int FWD_THREADS = 64 * FWD_WAVES;
 
 bool mfma_supported(const Dims& D) { return D.dtype == 1 && D.d == 128; }
-size_t attn_fwd_mfma_ws_bytes(const Dims&) { return 0; }
+size_t attn_fwd_mfma_ws_bytes(const Dims& D) { return compact_kv_bytes(D); }
+
+// Copies the K and V rows of every gather-list entry into the condensed cache: 16 lanes per row, 16 rows
+// per workgroup.
+__global__ __launch_bounds__(256) void k_compact_kv(Dims D, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+                                                    const int32_t* __restrict__ idx, bf16_t* __restrict__ Kc,
+                                                    bf16_t* __restrict__ Vc, int gl) {
+    const int j = blockIdx.x * 16 + (threadIdx.x >> 4), sub = threadIdx.x & 15;
+    const int bh = blockIdx.y;
+    if (j >= gl) return;
+    const int b = bh / D.Hkv, h = bh % D.Hkv;
+    const int pos = j < D.S ? j : idx[int64_t(bh) * D.Ns * D.K + (j - D.S)];
+    const int64_t src = b * D.ks[0] + h * D.ks[1] + int64_t(pos) * D.ks[2] + sub * 8;
+    const int64_t dst = (int64_t(bh) * gl + j) * 128 + sub * 8;
+    *reinterpret_cast<uint4*>(Kc + dst) = *reinterpret_cast<const uint4*>(K + src);
+    *reinterpret_cast<uint4*>(Vc + dst) = *reinterpret_cast<const uint4*>(V + src);
+}
+
+hipError_t launch_compact_kv(const Dims& D, const void* K, const void* V, const int32_t* idx, void* Kc, void* Vc,
+                             hipStream_t st) {
+    const int gl = gather_list_len(D);
+    if (gl == 0) return hipSuccess;
+    LRSA_TIMED_LAUNCH("k_compact_kv", st, k_compact_kv, dim3((gl + 15) / 16, D.B * D.Hkv), dim3(256), 0, st, D,
+                      (const bf16_t*)K, (const bf16_t*)V, idx, (bf16_t*)Kc, (bf16_t*)Vc, gl);
+    return hipGetLastError();
+}
 
 // One 64-key tile of the walk for one wave: S^T = K Q^T, masked online softmax, O^T += V^T P^T.
 struct FwdState {
@@ -122,11 +147,14 @@ __device__ __forceinline__ void fwd_tile(const unsigned char* sK, const unsigned
 
 // GH query heads of one KV group share the workgroup: its 8 waves cover GH heads x QT = 256/GH queries,
 // so every K/V tile staged in LDS serves 256 (head, query) rows.
-template <int GH>
+// COMPACT: the rows of the gather list come from the condensed cache Kc, Vc (contiguous), no index is read.
+template <int GH, bool COMPACT>
 __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_t* __restrict__ Q,
                                                               const bf16_t* __restrict__ K,
                                                               const bf16_t* __restrict__ V,
                                                               const int32_t* __restrict__ idx,
+                                                              const bf16_t* __restrict__ Kc,
+                                                              const bf16_t* __restrict__ Vc,
                                                               bf16_t* __restrict__ O, float* __restrict__ lse,
                                                               QTileMap M) {
     constexpr int WPH = FWD_WAVES / GH;   // waves per head
@@ -164,6 +192,9 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
     const bf16_t* Kh = K + b * D.ks[0] + h * D.ks[1];
     const bf16_t* Vh = V + b * D.ks[0] + h * D.ks[1];
     const int32_t* idx_h = idx + (int64_t(b) * D.Hkv + h) * D.Ns * D.K;
+    const int64_t coff = COMPACT ? (int64_t(b) * D.Hkv + h) * (int64_t(D.S) + int64_t(D.K) * D.Ns) * 128 : 0;
+    const bf16_t* Kc_h = Kc + coff;
+    const bf16_t* Vc_h = Vc + coff;
 
     // this lane's query column
     const int tq = t0 + wq * 32 + l32;
@@ -191,6 +222,7 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
         return e < 0 ? 0 : (e > idx_last ? idx_last : e);
     };
     auto fetch_pos = [&](int tile, Scalar8& raw) {
+        if (COMPACT) return;
         const int tc = tile < ntiles ? tile : ntiles - 1;   // past the end: repeat the last tile (never consumed)
         raw.a0 = smem_load(idx_ld, pos_entry(tc, 0)); raw.a1 = smem_load(idx_ld, pos_entry(tc, 1));
         raw.a2 = smem_load(idx_ld, pos_entry(tc, 2)); raw.a3 = smem_load(idx_ld, pos_entry(tc, 3));
@@ -200,17 +232,23 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
     auto issue = [&](int tile, Scalar8& raw, unsigned char* sK, unsigned char* sV) {
         const int tc = tile < ntiles ? tile : ntiles - 1;
         const int q4 = lane >> 4;
-        smem_wait(raw);
+        if (!COMPACT) smem_wait(raw);
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int r4 = 8 * wv + 4 * i;
             int j = tc * FWD_BN + r4 + q4;
             j = j < m_max ? j : m_max - 1;
-            const int sel = i == 0 ? pick4(q4, raw.a0, raw.a1, raw.a2, raw.a3) : pick4(q4, raw.a4, raw.a5, raw.a6, raw.a7);
-            const int pos = j < ng ? (j < D.S ? j : sel) : cs + (j - ng);
-            const int64_t off = int64_t(pos) * D.ks[2] + async_chunk(r4 + q4, lane) * 8;
-            async_rows4(Kh + off, sK, r4);
-            async_rows4(Vh + off, sV, r4);
+            const int ch = async_chunk(r4 + q4, lane) * 8;
+            if (COMPACT) {
+                async_rows4(stream_row(Kc_h, Kh, D.ks[2], j, ng, cs) + ch, sK, r4);
+                async_rows4(stream_row(Vc_h, Vh, D.ks[2], j, ng, cs) + ch, sV, r4);
+            } else {
+                const int sel = i == 0 ? pick4(q4, raw.a0, raw.a1, raw.a2, raw.a3) : pick4(q4, raw.a4, raw.a5, raw.a6, raw.a7);
+                const int pos = j < ng ? (j < D.S ? j : sel) : cs + (j - ng);
+                const int64_t off = int64_t(pos) * D.ks[2] + ch;
+                async_rows4(Kh + off, sK, r4);
+                async_rows4(Vh + off, sV, r4);
+            }
         }
     };
     constexpr int OPS_PER_TILE = 4;   // asynchronous copies per wave and tile
@@ -280,18 +318,27 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
 }
 
 hipError_t launch_attn_fwd_mfma(const Dims& D, const void* Q, const void* K, const void* V, const int32_t* idx,
-                                void* O, float* lse, void*, hipStream_t st) {
+                                void* O, float* lse, void* ws, hipStream_t st) {
     const int gh = heads_per_wg(D);
     const QTileMap M = make_qtile_map(D, gh, FWD_WAVES);
     const int64_t wgs = int64_t(D.B) * D.Hkv * M.per_unit;
     if (wgs == 0) return hipSuccess;
     const bf16_t *q = (const bf16_t*)Q, *k = (const bf16_t*)K, *v = (const bf16_t*)V;
-    if (gh == 4)
-        LRSA_TIMED_LAUNCH("k_fwd_mfma", st, k_fwd_mfma<4>, dim3((unsigned)wgs), dim3(FWD_THREADS), 0, st, D, q, k, v, idx, (bf16_t*)O, lse, M);
-    else if (gh == 2)
-        LRSA_TIMED_LAUNCH("k_fwd_mfma", st, k_fwd_mfma<2>, dim3((unsigned)wgs), dim3(FWD_THREADS), 0, st, D, q, k, v, idx, (bf16_t*)O, lse, M);
-    else
-        LRSA_TIMED_LAUNCH("k_fwd_mfma", st, k_fwd_mfma<1>, dim3((unsigned)wgs), dim3(FWD_THREADS), 0, st, D, q, k, v, idx, (bf16_t*)O, lse, M);
+    const bool compact = D.compact && gather_list_len(D) > 0;
+    const bf16_t *kc = nullptr, *vc = nullptr;
+    if (compact) {
+        kc = reinterpret_cast<const bf16_t*>(ws);
+        vc = reinterpret_cast<const bf16_t*>(reinterpret_cast<const char*>(ws) + compact_kv_bytes(D) / 2);
+        const hipError_t e = launch_compact_kv(D, K, V, idx, (void*)kc, (void*)vc, st);
+        if (e != hipSuccess) return e;
+    }
+#define LRSA_FWD_LAUNCH(GH_, C_)                                                                                   \
+    LRSA_TIMED_LAUNCH("k_fwd_mfma", st, (k_fwd_mfma<GH_, C_>), dim3((unsigned)wgs), dim3(FWD_THREADS), 0, st, D, q, k, v, \
+                      idx, kc, vc, (bf16_t*)O, lse, M)
+    if (gh == 4) { if (compact) LRSA_FWD_LAUNCH(4, true); else LRSA_FWD_LAUNCH(4, false); }
+    else if (gh == 2) { if (compact) LRSA_FWD_LAUNCH(2, true); else LRSA_FWD_LAUNCH(2, false); }
+    else { if (compact) LRSA_FWD_LAUNCH(1, true); else LRSA_FWD_LAUNCH(1, false); }
+#undef LRSA_FWD_LAUNCH
     return hipGetLastError();
 }
 

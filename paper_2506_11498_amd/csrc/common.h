@@ -13,6 +13,7 @@ struct Dims {
     int P, R, nq, Ns;
     float scale;
     int dtype;  // 0 fp32, 1 bf16
+    int compact;  // MFMA attention kernels read a condensed copy of the gather list's K/V rows
     int64_t qs[3], ks[3];
 };
 

@@ -230,6 +230,21 @@ __device__ __forceinline__ void decode_qtile(const QTileMap& M, const Dims& D, i
     tix = M.tiles - 1 - w / M.gsubs;   // heaviest (latest) query tile first
 }
 
+// ---- condensed KV cache --------------------------------------------------------------------------
+// Kc, Vc [B, Hkv, gl, 128] bf16, contiguous: row j of a head is the K (V) row of entry j of its gather list
+// (sink tokens, then the survivors chunk by chunk); gl = S + K * Ns.
+inline int gather_list_len(const Dims& D) { return D.nq > 0 ? D.S + D.K * D.Ns : 0; }
+inline size_t compact_kv_bytes(const Dims& D) {
+    return D.compact ? 2 * align256(size_t(D.B) * D.Hkv * gather_list_len(D) * 128 * sizeof(bf16_t)) : 0;
+}
+hipError_t launch_compact_kv(const Dims& D, const void* K, const void* V, const int32_t* idx, void* Kc, void* Vc,
+                             hipStream_t st);
+// address of the row of stream entry j (gather list, then the contiguous window) with a condensed cache
+__device__ __forceinline__ const bf16_t* stream_row(const bf16_t* Zc, const bf16_t* Z, int64_t stride, int j, int ng,
+                                                    int cs) {
+    return j < ng ? Zc + int64_t(j) * 128 : Z + int64_t(cs + (j - ng)) * stride;
+}
+
 // heads of a group that share a workgroup: the largest of 4, 2, 1 that divides the group size
 inline int heads_per_wg(const Dims& D) { return D.G % 4 == 0 ? 4 : D.G % 2 == 0 ? 2 : 1; }
 

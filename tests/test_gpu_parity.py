@@ -176,6 +176,32 @@ def test_fused_score_select_equals_the_two_calls_and_the_oracle(cfg):
         check_selection_in_tie_window(w, idx_f.cpu().numpy(), idx_ref, sc_ref)
 
 
+@pytest.mark.parametrize("cfg", [
+    dict(n=16 + 6 * 64 + 40, L=64, S=16, K=16, d=128, Hq=8, Hkv=2, B=2, dtype="bf16"),
+    dict(n=5 + 7 * 100 + 33, L=100, S=5, K=37, d=128, Hq=2, Hkv=1, B=1, dtype="bf16"),
+    dict(n=3 + 6 * 48 + 5, L=48, S=3, K=12, d=128, Hq=6, Hkv=2, B=1, dtype="bf16"),
+    dict(n=40, L=32, S=64, K=8, d=128, Hq=2, Hkv=1, B=1, dtype="bf16"),                 # no gather list at all
+    dict(n=4 + 6 * 16, L=16, S=4, K=5, d=64, Hq=4, Hkv=2, B=1, dtype="f32"),            # generic kernels: flag ignored
+], ids=["gqa", "odd_sizes", "group_of_3", "sink_only", "f32_generic"])
+def test_condensed_kv_cache_variant_is_bit_identical(cfg):
+    """impl = COMPACT (rows of the gather list copied into a contiguous buffer first) against impl = AUTO
+    (rows gathered by index inside the kernels): the same rows in the same order, so the same bits."""
+    w = inputs.small_workload(**cfg)
+    x = inputs.make_inputs(w)
+    xd = {k: v.to(DEV) for k, v in x.items()}
+    p, score, idx = run_score_select(w, xd)
+    pc = params(w, xd, impl=lrsa.IMPL_COMPACT)
+    assert lrsa.workspace_bytes(pc, 3) >= lrsa.workspace_bytes(p, 3)
+    idx_arg = idx if lrsa.num_scored_chunks(p) else None
+    O, lse = lrsa.lrsa_attn_fwd(p, xd["Q"], xd["K"], xd["V"], idx_arg)
+    Oc, lsec = lrsa.lrsa_attn_fwd(pc, xd["Q"], xd["K"], xd["V"], idx_arg)
+    assert torch.equal(O, Oc) and torch.equal(lse, lsec)
+    g = lrsa.lrsa_attn_bwd(p, xd["Q"], xd["K"], xd["V"], O, xd["dO"], lse, idx_arg)
+    gc = lrsa.lrsa_attn_bwd(pc, xd["Q"], xd["K"], xd["V"], O, xd["dO"], lse, idx_arg)
+    for a, b in zip(g, gc):
+        assert torch.equal(a, b)
+
+
 def test_strided_views_and_preallocated_outputs():
     """Q/K/V given as [B, n, H, d] storage viewed as [B, H, n, d] (position stride = H*d)."""
     w = inputs.small_workload(n=8 + 5 * 32 + 3, L=32, S=8, K=8, d=128, Hq=4, Hkv=2, B=2, dtype="bf16")
