@@ -290,11 +290,11 @@ def test_workload_C2_small_bf16():
 
 
 def test_workload_C3_llama7b_shaped():
-    full_workload_parity("C3", kv_heads=[7], n_rows=192, n_cols=48)
+    full_workload_parity("C3", kv_heads=[7, 20], n_rows=128, n_cols=32)
 
 
 def test_workload_C4_gqa_32k():
-    full_workload_parity("C4", kv_heads=[3], n_rows=192, n_cols=32)
+    full_workload_parity("C4", kv_heads=[0, 3, 7], n_rows=96, n_cols=16)
 
 
 def test_workload_C6_paper_training_shape():
@@ -302,4 +302,4 @@ def test_workload_C6_paper_training_shape():
 
 
 def test_workload_C5_stress_128k():
-    full_workload_parity("C5", kv_heads=[6], n_rows=96, n_cols=12, late_cols_only=True)
+    full_workload_parity("C5", kv_heads=[1, 6], n_rows=64, n_cols=8, late_cols_only=True)
