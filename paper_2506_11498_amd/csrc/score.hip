@@ -11,6 +11,7 @@
 // All arithmetic is fp32 on the stored values with correctly rounded division and square root, two-pass
 // variance, max-subtracted softmax.  Rows are read with 16-byte loads, a row being spread over
 // consecutive lanes so that a wave reads whole rows back to back.
+#include "score_block.h"
 #include "select_block.h"
 
 namespace lrsa {
@@ -179,167 +180,25 @@ __global__ __launch_bounds__(SCORE_THREADS) void k_softmax(Dims D, const float* 
 // chunk, so the second read is served by L2 / the memory-side cache.  The division of Eq. 6 is done as
 // a multiplication by the correctly rounded reciprocal plus one fused residual correction
 // (q + (a - b*q) * rcp), which reproduces the IEEE quotient.
-constexpr int FUSED_THREADS = 1024;
-constexpr int FUSED_MAX_L = 4096;
-
-// SELECT: the workgroup also takes the top K of the chunk it has just scored (the scores are still in LDS).
+// One workgroup per (batch, KV head, chunk p).  SELECT: the workgroup also takes the top K of the chunk it has
+// just scored (the scores are still in LDS).
 template <typename T, bool SELECT>
 __global__ __launch_bounds__(FUSED_THREADS) void k_score_fused(Dims D, const T* __restrict__ Kp,
                                                                const T* __restrict__ Vp,
                                                                float* __restrict__ score, int32_t* __restrict__ idx) {
-    constexpr int VEC = Elem<T>::VEC;
-    constexpr int NW = FUSED_THREADS / 64;
-    const int lpr = D.d / VEC;                // lanes per row
-    const int rpp = FUSED_THREADS / lpr;      // rows per pass
     const int p = blockIdx.x, bh = blockIdx.y;
     const int b = bh / D.Hkv, h = bh % D.Hkv;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int sub = tid % lpr, rg = tid / lpr;
     const int64_t hoff = b * D.ks[0] + h * D.ks[1];
-    const int64_t ref0 = int64_t(D.S) + int64_t(p + 1) * D.L;   // first row of the reference chunk
     const int64_t cur0 = int64_t(D.S) + int64_t(p) * D.L;       // first row of the scored chunk
-
-    __shared__ float red[4][NW][128];     // per-wave partial min_K, max_K, min_V, max_V
-    __shared__ float s_mn[2][128], s_inv[2][128], s_den[2][128];
-    __shared__ float sig[2][FUSED_MAX_L];
-    __shared__ float sm[NW];
-
-    // ---- phase 1
-    {
-        float mn[2][VEC], mx[2][VEC];
-#pragma unroll
-        for (int z = 0; z < 2; ++z)
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) { mn[z][i] = INFINITY; mx[z][i] = -INFINITY; }
-        for (int r = rg; r < D.L; r += 2 * rpp) {
-            // two rows of K and of V in flight
-            const int r2 = r + rpp < D.L ? r + rpp : r;
-            float k0[VEC], k1[VEC], v0[VEC], v1[VEC];
-            Elem<T>::load(Kp + hoff + (ref0 + r) * D.ks[2] + sub * VEC, k0);
-            Elem<T>::load(Vp + hoff + (ref0 + r) * D.ks[2] + sub * VEC, v0);
-            Elem<T>::load(Kp + hoff + (ref0 + r2) * D.ks[2] + sub * VEC, k1);
-            Elem<T>::load(Vp + hoff + (ref0 + r2) * D.ks[2] + sub * VEC, v1);
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) {
-                mn[0][i] = fminf(mn[0][i], fminf(k0[i], k1[i])); mx[0][i] = fmaxf(mx[0][i], fmaxf(k0[i], k1[i]));
-                mn[1][i] = fminf(mn[1][i], fminf(v0[i], v1[i])); mx[1][i] = fmaxf(mx[1][i], fmaxf(v0[i], v1[i]));
-            }
-        }
-        // lanes of one wave that hold the same channels (different rows): shuffle over the row groups
-        for (int o = lpr; o < 64; o <<= 1)
-#pragma unroll
-            for (int z = 0; z < 2; ++z)
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) {
-                    mn[z][i] = fminf(mn[z][i], __shfl_xor(mn[z][i], o, 64));
-                    mx[z][i] = fmaxf(mx[z][i], __shfl_xor(mx[z][i], o, 64));
-                }
-        if (lane < lpr) {
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) {
-                red[0][wave][lane * VEC + i] = mn[0][i]; red[1][wave][lane * VEC + i] = mx[0][i];
-                red[2][wave][lane * VEC + i] = mn[1][i]; red[3][wave][lane * VEC + i] = mx[1][i];
-            }
-        }
-        __syncthreads();
-        if (tid < 2 * D.d) {
-            const int z = tid / D.d, c = tid % D.d;
-            float a = INFINITY, m = -INFINITY;
-            for (int w = 0; w < NW; ++w) { a = fminf(a, red[2 * z][w][c]); m = fmaxf(m, red[2 * z + 1][w][c]); }
-            float den = m - a;
-            den = den == 0.0f ? 1.0f : den;
-            s_mn[z][c] = a;
-            s_den[z][c] = den;
-            s_inv[z][c] = 1.0f / den;
-        }
-        __syncthreads();
-    }
-    // ---- phase 2: sigma of every row of chunk p; two rows of K and of V in flight per thread
-    {
-        float mn[2][VEC], den[2][VEC], inv[2][VEC];
-#pragma unroll
-        for (int z = 0; z < 2; ++z)
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) {
-                mn[z][i] = s_mn[z][sub * VEC + i]; den[z][i] = s_den[z][sub * VEC + i]; inv[z][i] = s_inv[z][sub * VEC + i];
-            }
-        for (int r = rg; r < D.L; r += 2 * rpp) {
-            const bool has2 = r + rpp < D.L;
-            const int r2 = has2 ? r + rpp : r;
-            float x[4][VEC];   // K row r, K row r2, V row r, V row r2
-            Elem<T>::load(Kp + hoff + (cur0 + r) * D.ks[2] + sub * VEC, x[0]);
-            Elem<T>::load(Kp + hoff + (cur0 + r2) * D.ks[2] + sub * VEC, x[1]);
-            Elem<T>::load(Vp + hoff + (cur0 + r) * D.ks[2] + sub * VEC, x[2]);
-            Elem<T>::load(Vp + hoff + (cur0 + r2) * D.ks[2] + sub * VEC, x[3]);
-            float sm4[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int z = j >> 1;
-                float acc = 0.0f;
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) {
-                    const float a0 = x[j][i] - mn[z][i];
-                    float q0 = a0 * inv[z][i];
-                    q0 = __builtin_fmaf(__builtin_fmaf(-den[z][i], q0, a0), inv[z][i], q0);   // correctly rounded a0 / den
-                    x[j][i] = q0;
-                    acc += q0;
-                }
-                sm4[j] = acc;
-            }
-            for (int o = lpr >> 1; o > 0; o >>= 1)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) sm4[j] += __shfl_xor(sm4[j], o, 64);
-            float var4[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float m = sm4[j] / float(D.d);
-                float acc = 0.0f;
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) { const float dd = x[j][i] - m; acc += dd * dd; }
-                var4[j] = acc;
-            }
-            for (int o = lpr >> 1; o > 0; o >>= 1)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) var4[j] += __shfl_xor(var4[j], o, 64);
-            if (sub == 0) {
-                sig[0][r] = sqrtf(var4[0] / float(D.d - D.ddof));
-                sig[1][r] = sqrtf(var4[2] / float(D.d - D.ddof));
-                if (has2) {
-                    sig[0][r2] = sqrtf(var4[1] / float(D.d - D.ddof));
-                    sig[1][r2] = sqrtf(var4[3] / float(D.d - D.ddof));
-                }
-            }
-        }
-        __syncthreads();
-    }
-    // ---- phase 3
-    auto block_red = [&](float v, bool is_max) {
-        v = is_max ? wave_max(v) : wave_sum(v);
-        __syncthreads();
-        if (lane == 0) sm[wave] = v;
-        __syncthreads();
-        float r = sm[0];
-        for (int i = 1; i < NW; ++i) r = is_max ? fmaxf(r, sm[i]) : r + sm[i];
-        return r;
-    };
-    float mk = -INFINITY, mv = -INFINITY;
-    for (int r = tid; r < D.L; r += FUSED_THREADS) { mk = fmaxf(mk, sig[0][r]); mv = fmaxf(mv, sig[1][r]); }
-    mk = block_red(mk, true);
-    mv = block_red(mv, true);
-    float zk = 0.0f, zv = 0.0f;
-    for (int r = tid; r < D.L; r += FUSED_THREADS) { zk += expf(sig[0][r] - mk); zv += expf(sig[1][r] - mv); }
-    zk = block_red(zk, false);
-    zv = block_red(zv, false);
-    float* out = score + (int64_t(bh) * D.Ns + p) * D.L;
-    for (int r = tid; r < D.L; r += FUSED_THREADS) {
-        const float sc = expf(sig[0][r] - mk) / zk + expf(sig[1][r] - mv) / zv;
-        out[r] = sc;
-        if (SELECT) sig[0][r] = sc;     // each thread overwrites only what it alone has read
-    }
+    const int64_t ref0 = cur0 + D.L;                             // first row of the reference chunk p+1
+    __shared__ ScoreLds sh;
+    score_chunk_block<T>(D.L, D.d, D.ddof, Kp + hoff + cur0 * D.ks[2], Kp + hoff + ref0 * D.ks[2],
+                         Vp + hoff + cur0 * D.ks[2], Vp + hoff + ref0 * D.ks[2], D.ks[2], sh,
+                         score + (int64_t(bh) * D.Ns + p) * D.L);
     if (SELECT) {
         __shared__ SelectLds sel;
         __syncthreads();
-        select_topk_block<FUSED_THREADS>(reinterpret_cast<const uint32_t*>(sig[0]), D.L, D.K, D.S + p * D.L,
+        select_topk_block<FUSED_THREADS>(reinterpret_cast<const uint32_t*>(sh.sig[0]), D.L, D.K, D.S + p * D.L,
                                          idx + (int64_t(bh) * D.Ns + p) * D.K, sel);
     }
 }
