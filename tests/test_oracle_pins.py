@@ -427,3 +427,47 @@ def test_inputs_are_seeded_and_sliceable():
     w4 = inputs.WORKLOADS["C4"].with_(n=4096, Hq=4, Hkv=1)
     drift = inputs.make_tensor(w4, "K").float() - inputs.make_tensor(w4, "K", structured=False).float()
     assert drift[0, 0, 0].abs().max() < 0.02 and 0.2 < drift[0, 0, -1].std() < 1.5
+
+
+# ------------------------------------------------------------------ inference-time cache (oracle/lrsa_decode.py)
+def test_incremental_cache_equals_gather_list_plus_window():
+    """Token-by-token compression of the cache must leave exactly what the training-time mask lets the
+    last query see: the sink, the survivors of the compressed chunks (the selection depends only on the
+    original rows of a chunk and of the chunk after it), the previous chunk in full and the own chunk --
+    with and without a tail, exactly at a chunk boundary and one token past it."""
+    from oracle import lrsa_decode as dec
+    rng = np.random.default_rng(11)
+    for (n, S, L, K) in [(3 + 5 * 8 + 5, 3, 8, 3), (4 + 6 * 8, 4, 8, 2), (0 + 4 * 6 + 1, 0, 6, 6),
+                         (2 + 2 * 8 - 1, 2, 8, 4), (2 + 2 * 8 + 1, 2, 8, 4), (5, 9, 8, 4)]:
+        Kh = rng.standard_normal((n, 16)).astype(np.float32)
+        Vh = rng.standard_normal((n, 16)).astype(np.float32)
+        Kc, Vc, pos, done = dec.cache_incremental(Kh, Vh, S, L, K)
+        part = ref.partition(n, S, L)
+        assert done == part["Ns"]
+        if part["Ns"]:
+            idx = ref.select(ref.score(Kh[None, None], Vh[None, None], S, L), S, L, K)[0, 0]
+        else:
+            idx = np.zeros((0, K), np.int32)
+        want = np.concatenate([np.arange(min(S, n)), idx.reshape(-1), np.arange(S + L * done, n)]) if n > S else np.arange(n)
+        assert np.array_equal(pos, want)
+        assert np.array_equal(Kc, Kh[pos]) and np.array_equal(Vc, Vh[pos])
+        # ... which is the visible set of the last row of the training-time mask
+        vis = np.flatnonzero(ref.visible_mask(n, S, L, idx if part["Ns"] else None)[n - 1])
+        assert np.array_equal(np.sort(pos), vis)
+
+
+def test_decode_attention_equals_last_row_of_the_masked_attention():
+    from oracle import lrsa_decode as dec
+    rng = np.random.default_rng(12)
+    n, S, L, K, d, G = 2 + 5 * 8 + 3, 2, 8, 3, 16, 3
+    Q = rng.standard_normal((1, G, n, d)); Kh = rng.standard_normal((1, 1, n, d)).astype(np.float32)
+    Vh = rng.standard_normal((1, 1, n, d)).astype(np.float32)
+    idx = ref.select(ref.score(Kh, Vh, S, L), S, L, K)
+    O_ref, lse_ref = ref.attn_fwd_dense(Q, Kh, Vh, idx, S, L)
+    Kc, Vc, pos, done = dec.cache_incremental(Kh[0, 0], Vh[0, 0], S, L, K)
+    O, lse = dec.decode_attn(Q[0, :, n - 1], Kc, Vc)
+    assert np.allclose(O, O_ref[0, :, n - 1], rtol=1e-12, atol=1e-12)
+    assert np.allclose(lse, lse_ref[0, :, n - 1], rtol=1e-12, atol=1e-12)
+    # closed form: one key -> the output is that key's value row, lse = the logit
+    O1, l1 = dec.decode_attn(Q[0, :, 0], Kh[0, 0, :1], Vh[0, 0, :1])
+    assert np.allclose(O1, np.repeat(Vh[0, 0, :1], G, 0)) and np.allclose(l1, Q[0, :, 0] @ Kh[0, 0, 0] / np.sqrt(d))
