@@ -77,7 +77,10 @@ typedef struct {
 } lrsa_params;
 
 /* Which call a workspace size is asked for. */
-typedef enum { LRSA_WS_SCORE = 0, LRSA_WS_SELECT = 1, LRSA_WS_ATTN_FWD = 2, LRSA_WS_ATTN_BWD = 3 } lrsa_ws_kind;
+typedef enum {
+    LRSA_WS_SCORE = 0, LRSA_WS_SELECT = 1, LRSA_WS_ATTN_FWD = 2, LRSA_WS_ATTN_BWD = 3,
+    LRSA_WS_DECODE_ATTN = 4 /* lrsa_decode_attn; lrsa_cache_compress needs none */
+} lrsa_ws_kind;
 
 /* Ns of the partition above; pure host arithmetic.  Returns a negative lrsa_status on bad params. */
 int lrsa_num_scored_chunks(const lrsa_params *p);
@@ -136,6 +139,36 @@ int lrsa_attn_fwd(const lrsa_params *p, const void *Q, const void *K, const void
 int lrsa_attn_bwd(const lrsa_params *p, const void *Q, const void *K, const void *V, const void *O,
                   const void *dO, const float *lse, const int32_t *idx,
                   void *dQ, void *dK, void *dV, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- inference-time LagKV cache (the setting of the paper's evaluation: the cache compressed lag window by
+ * lag window while tokens are generated; "the KV cache is updated with the first chunk compressed and the
+ * second chunk retained as a sliding window", Attention Filling 1).
+ *
+ * Cache of one layer: Kc, Vc [B, Hkv, cap, d_h] by kv_stride with cap = p->seq; rows [0, len) valid, the same
+ * len for every head: the sink rows, then topk rows per compressed chunk, then the uncompressed tail.
+ * heads_q, sink, lag, topk, std_ddof, dtype as for the other calls; local_prev must be 1; lag <= 4096.
+ *
+ * lrsa_cache_compress: while the tail holds at least 2*lag rows, the first lag rows of the tail are scored
+ * against the next lag rows (Eq. 4-8), their top `topk` rows are kept in position order (text after Eq. 8,
+ * ties to the lowest position) and the rest of the tail moves down, in place.  Call it BEFORE appending the
+ * next token: a token attends first, the chunk before its own is compressed only when the following token
+ * arrives -- the cache is then exactly what the training-time mask lets that token see.
+ *   Kc, Vc : device, read and written in place
+ *   pos    : [B, Hkv, cap] int32, contiguous, the original position of every row; moved alike; may be NULL
+ *   len, done : valid rows and chunks compressed so far (host values)
+ *   len_out, done_out : HOST pointers, receive the new values (pure host arithmetic, no synchronisation)
+ * Nothing is launched when the tail is shorter than 2*lag. */
+int lrsa_cache_compress(const lrsa_params *p, void *Kc, void *Vc, int32_t *pos, int32_t len, int32_t done,
+                        int32_t *len_out, int32_t *done_out, void *stream);
+
+/* Single-query attention over the cache (Eq. 3, every cache row visible): for each query head,
+ * O = softmax(scale q.Kc^T) Vc over rows [0, len).  Query head hq reads KV head hq / G.
+ *   q   : [B, Hq, d_h] contiguous, dtype `dtype`                                  (device, read)
+ *   O   : [B, Hq, d_h] contiguous, dtype `dtype`                                  (device, written)
+ *   lse : [B, Hq] fp32 log-sum-exp of the scaled logits, may be NULL              (device, written)
+ * 1 <= len <= cap.  Workspace: LRSA_WS_DECODE_ATTN. */
+int lrsa_decode_attn(const lrsa_params *p, const void *q, const void *Kc, const void *Vc, int32_t len, void *O,
+                     float *lse, void *ws, size_t ws_bytes, void *stream);
 
 /* Message of the calling thread's last failed call (static thread-local storage, never NULL). */
 const char *lrsa_last_error(void);

@@ -18,10 +18,11 @@ LIB_PATH = os.environ.get("LRSA_LIB", os.path.join(_HERE, "liblrsa.so"))
 
 LRSA_F32, LRSA_BF16 = 0, 1
 IMPL_AUTO, IMPL_GENERIC, IMPL_COMPACT = 0, 1, 2
-WS_SCORE, WS_SELECT, WS_ATTN_FWD, WS_ATTN_BWD = 0, 1, 2, 3
+WS_SCORE, WS_SELECT, WS_ATTN_FWD, WS_ATTN_BWD, WS_DECODE_ATTN = 0, 1, 2, 3, 4
 
 EXPORTS = ("lrsa_abi_version", "lrsa_last_error", "lrsa_num_scored_chunks", "lrsa_workspace_bytes",
            "lrsa_score", "lrsa_select", "lrsa_score_select", "lrsa_attn_fwd", "lrsa_attn_bwd",
+           "lrsa_cache_compress", "lrsa_decode_attn",
            "lrsa_timing_enable", "lrsa_timing_count", "lrsa_timing_read")
 
 
@@ -62,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.lrsa_score.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.lrsa_select.argtypes = [vp, vp, vp, vp, sz, vp]
         L.lrsa_score_select.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
+        L.lrsa_cache_compress.argtypes = [vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp]
+        L.lrsa_decode_attn.argtypes = [vp, vp, vp, vp, ctypes.c_int32, vp, vp, vp, sz, vp]
         L.lrsa_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.lrsa_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         _lib = L
@@ -155,6 +158,30 @@ def lrsa_score_select(p: LrsaParams, K: torch.Tensor, V: torch.Tensor, score: Op
     ws, nb = _workspace(p, WS_SCORE, K.device, ws)
     _check(lib().lrsa_score_select(ctypes.byref(p), _ptr(K), _ptr(V), _ptr(score), _ptr(idx), _ptr(ws), nb, _stream()))
     return score, idx
+
+
+def lrsa_cache_compress(p: LrsaParams, Kc: torch.Tensor, Vc: torch.Tensor, pos: Optional[torch.Tensor],
+                        length: int, done: int):
+    """Inference-time cache: compress (in place) while the uncompressed tail holds 2*lag rows.
+    Kc, Vc: [B, Hkv, cap, d] with cap = p.seq; pos: int32 [B, Hkv, cap] or None.  Returns (length, done)."""
+    new_len, new_done = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().lrsa_cache_compress(ctypes.byref(p), _ptr(Kc), _ptr(Vc), _ptr(pos), int(length), int(done),
+                                     ctypes.byref(new_len), ctypes.byref(new_done), _stream()))
+    return new_len.value, new_done.value
+
+
+def lrsa_decode_attn(p: LrsaParams, q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, length: int,
+                     O: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                     ws: Optional[torch.Tensor] = None):
+    """Single-query attention over cache rows [0, length): q, O [B, Hq, d]; returns (O, lse [B, Hq] fp32)."""
+    if O is None:
+        O = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((p.batch, p.heads_q), dtype=torch.float32, device=q.device)
+    ws, nb = _workspace(p, WS_DECODE_ATTN, q.device, ws)
+    _check(lib().lrsa_decode_attn(ctypes.byref(p), _ptr(q), _ptr(Kc), _ptr(Vc), int(length), _ptr(O), _ptr(lse),
+                                  _ptr(ws), nb, _stream()))
+    return O, lse
 
 
 def lrsa_attn_fwd(p: LrsaParams, Q, K, V, idx, O: Optional[torch.Tensor] = None,

@@ -77,6 +77,7 @@ size_t ws_need(const lrsa_params* p, const lrsa::Dims& D, int which) {
         case LRSA_WS_SELECT: return lrsa::select_ws_bytes(D);
         case LRSA_WS_ATTN_FWD: return use_mfma(p, D) ? lrsa::attn_fwd_mfma_ws_bytes(D) : lrsa::attn_fwd_generic_ws_bytes(D);
         case LRSA_WS_ATTN_BWD: return use_mfma(p, D) ? lrsa::attn_bwd_mfma_ws_bytes(D) : lrsa::attn_bwd_generic_ws_bytes(D);
+        case LRSA_WS_DECODE_ATTN: return lrsa::decode_ws_bytes(D);
         default: return 0;
     }
 }
@@ -151,6 +152,39 @@ int lrsa_score_select(const lrsa_params* p, const void* K, const void* V, float*
         return fail(LRSA_ERR_INVALID_ARG, "lrsa_score_select: K and V must be 16-byte aligned");
     if ((rc = check_ws(p, D, LRSA_WS_SCORE, ws, ws_bytes)) != LRSA_OK) return rc;
     return hip_result(lrsa::launch_score_select(D, K, V, score, idx, ws, (hipStream_t)stream), "lrsa_score_select");
+}
+
+int lrsa_cache_compress(const lrsa_params* p, void* Kc, void* Vc, int32_t* pos, int32_t len, int32_t done,
+                        int32_t* len_out, int32_t* done_out, void* stream) {
+    lrsa::Dims D;
+    int rc = make_dims(p, &D);
+    if (rc != LRSA_OK) return rc;
+    if (!len_out || !done_out) return fail(LRSA_ERR_INVALID_ARG, "lrsa_cache_compress: len_out and done_out must not be NULL");
+    if (!lrsa::cache_compress_supported(D))
+        return fail(LRSA_ERR_UNSUPPORTED, "lrsa_cache_compress needs local_prev == 1 and lag <= 4096");
+    if (len < 0 || len > D.n || done < 0) return fail(LRSA_ERR_INVALID_ARG, "lrsa_cache_compress: len %d outside [0, cap=%d] or done < 0", len, D.n);
+    const int64_t tail = (int64_t)len - D.S - (int64_t)D.K * done;
+    if (done > 0 && tail < D.L) return fail(LRSA_ERR_INVALID_ARG, "lrsa_cache_compress: len %d is too short for %d compressed chunks", len, done);
+    int steps = tail >= 2 * (int64_t)D.L ? (int)(tail / D.L) - 1 : 0;
+    *len_out = len - steps * (D.L - D.K);
+    *done_out = done + steps;
+    if (steps == 0) return LRSA_OK;
+    if (!Kc || !Vc) return fail(LRSA_ERR_INVALID_ARG, "lrsa_cache_compress: Kc and Vc must not be NULL");
+    if (misaligned16(Kc) || misaligned16(Vc)) return fail(LRSA_ERR_INVALID_ARG, "lrsa_cache_compress: Kc and Vc must be 16-byte aligned");
+    return hip_result(lrsa::launch_cache_compress(D, Kc, Vc, pos, len, done, steps, (hipStream_t)stream), "lrsa_cache_compress");
+}
+
+int lrsa_decode_attn(const lrsa_params* p, const void* q, const void* Kc, const void* Vc, int32_t len, void* O,
+                     float* lse, void* ws, size_t ws_bytes, void* stream) {
+    lrsa::Dims D;
+    int rc = make_dims(p, &D);
+    if (rc != LRSA_OK) return rc;
+    if (len < 1 || len > D.n) return fail(LRSA_ERR_INVALID_ARG, "lrsa_decode_attn: len %d outside [1, cap=%d]", len, D.n);
+    if (!q || !Kc || !Vc || !O) return fail(LRSA_ERR_INVALID_ARG, "lrsa_decode_attn: q, Kc, Vc and O must not be NULL");
+    if (misaligned16(q) || misaligned16(Kc) || misaligned16(Vc))
+        return fail(LRSA_ERR_INVALID_ARG, "lrsa_decode_attn: q, Kc and Vc must be 16-byte aligned");
+    if ((rc = check_ws(p, D, LRSA_WS_DECODE_ATTN, ws, ws_bytes)) != LRSA_OK) return rc;
+    return hip_result(lrsa::launch_decode_attn(D, q, Kc, Vc, len, O, lse, ws, (hipStream_t)stream), "lrsa_decode_attn");
 }
 
 int lrsa_attn_fwd(const lrsa_params* p, const void* Q, const void* K, const void* V, const int32_t* idx, void* O,

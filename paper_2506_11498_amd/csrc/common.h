@@ -36,6 +36,11 @@ hipError_t launch_score(const Dims&, const void* K, const void* V, float* score,
 
 size_t select_ws_bytes(const Dims&);
 hipError_t launch_select(const Dims&, const float* score, int32_t* idx, void* ws, hipStream_t st);
+size_t decode_ws_bytes(const Dims&);
+bool cache_compress_supported(const Dims&);
+hipError_t launch_cache_compress(const Dims&, void* Kc, void* Vc, int32_t* pos, int len, int done, int steps, hipStream_t st);
+hipError_t launch_decode_attn(const Dims&, const void* q, const void* Kc, const void* Vc, int len, void* O, float* lse,
+                              void* ws, hipStream_t st);
 hipError_t launch_score_select(const Dims&, const void* K, const void* V, float* score, int32_t* idx, void* ws, hipStream_t st);
 
 size_t attn_fwd_generic_ws_bytes(const Dims&);
