@@ -21,6 +21,7 @@ constexpr int DEC_THREADS = 256;
 constexpr int DEC_WAVES = DEC_THREADS / 64;
 constexpr int DEC_GMAX = 8;            // query heads of a group handled per pass
 constexpr int DEC_MAX_SPLITS = 256;
+constexpr int DEC_U = 4;               // rows per lane group and step
 
 static int decode_splits(const Dims& D, int len) {
     // enough workgroups to occupy the chip, at least 256 rows each
@@ -150,25 +151,49 @@ __global__ __launch_bounds__(DEC_THREADS) void k_decode_attn(Dims D, const T* __
             for (int i = 0; i < VEC; ++i) { o[g][i] = 0.0f; qv[g][i] = 0.0f; }
             if (g < gn) Elem<T>::load(q + (int64_t(b) * D.Hq + h * D.G + g0 + g) * D.d + sub * VEC, qv[g]);
         }
-        for (int r = r0 + wave * rpw + slot; r < r1; r += DEC_WAVES * rpw) {
-            float kv[VEC], vv[VEC];
-            Elem<T>::load(Kh + int64_t(r) * D.ks[2] + sub * VEC, kv);
-            Elem<T>::load(Vh + int64_t(r) * D.ks[2] + sub * VEC, vv);
+        // DEC_U rows per lane group and step: their loads are in flight together, and the running maximum is
+        // refreshed (and the sums rescaled) once per step instead of once per row
+        const int step = DEC_WAVES * rpw;
+        for (int rb = r0 + wave * rpw + slot; rb < r1; rb += DEC_U * step) {
+            float kv[DEC_U][VEC], vv[DEC_U][VEC];
+#pragma unroll
+            for (int u = 0; u < DEC_U; ++u) {
+                const int r = min(rb + u * step, r1 - 1);   // rows past the end repeat the last one, weight 0 below
+                Elem<T>::load(Kh + int64_t(r) * D.ks[2] + sub * VEC, kv[u]);
+                Elem<T>::load(Vh + int64_t(r) * D.ks[2] + sub * VEC, vv[u]);
+            }
 #pragma unroll
             for (int g = 0; g < DEC_GMAX; ++g) {
                 if (g >= gn) continue;
-                float s = 0.0f;
+                float sc[DEC_U], mn = m[g];
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) s = __builtin_fmaf(qv[g][i], kv[i], s);
-                for (int off = lpr >> 1; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-                s *= c2;
-                const float mn = fmaxf(m[g], s);
-                const float a = __builtin_amdgcn_exp2f(m[g] - mn);   // exp2(-inf) = 0 on the first row
-                const float pr = __builtin_amdgcn_exp2f(s - mn);
-                l[g] = l[g] * a + pr;
+                for (int u = 0; u < DEC_U; ++u) {
+                    float t = 0.0f;
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) t = __builtin_fmaf(qv[g][i], kv[u][i], t);
+                    sc[u] = t;
+                }
+                for (int off = lpr >> 1; off > 0; off >>= 1)
+#pragma unroll
+                    for (int u = 0; u < DEC_U; ++u) sc[u] += __shfl_xor(sc[u], off, 64);
+#pragma unroll
+                for (int u = 0; u < DEC_U; ++u) {
+                    sc[u] = rb + u * step < r1 ? sc[u] * c2 : -INFINITY;
+                    mn = fmaxf(mn, sc[u]);
+                }
+                const float a = __builtin_amdgcn_exp2f(m[g] - mn);   // exp2(-inf) = 0 on the first step; row rb is valid
+                float ls = 0.0f;
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) o[g][i] *= a;
+#pragma unroll
+                for (int u = 0; u < DEC_U; ++u) {
+                    const float pr = __builtin_amdgcn_exp2f(sc[u] - mn);
+                    ls += pr;
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) o[g][i] = __builtin_fmaf(pr, vv[u][i], o[g][i]);
+                }
+                l[g] = l[g] * a + ls;
                 m[g] = mn;
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) o[g][i] = __builtin_fmaf(pr, vv[i], o[g][i] * a);
             }
         }
         // merge the row slots of a wave, then the waves
