@@ -30,6 +30,7 @@ constexpr int BWD_THREADS = 256;
 constexpr int KV_WAVES = LRSA_KV_WAVES;   // waves per workgroup of the key-outer kernel
 constexpr int KV_THREADS = 64 * KV_WAVES;
 constexpr int DQ_BN = 64;
+constexpr int DQ_PF = 4;                 // LDS operands of the query-outer kernel are read this many MFMAs ahead
 constexpr int DQ_WAVES = 8;              // waves per workgroup of the query-outer kernel (two per SIMD)
 constexpr int DQ_THREADS = 64 * DQ_WAVES;
 constexpr int KV_NB = LRSA_KV_NB;               // 32-key blocks per wave
@@ -114,46 +115,46 @@ __device__ __forceinline__ void dq_tile(const unsigned char* sK, const unsigned 
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
         if (!MASK || j0 + kb * 32 <= wave_lim_max) {  // otherwise these 32 keys are masked for the whole wave
+            // 24 MFMAs: S^T (K rows), dA^T (V rows), dQ^T (K transposed, rows 0-15 then 16-31); their LDS operands
+            // form one stream that is read DQ_PF ahead.  A = exp2(S*c2 - lse2) is written beside the dA MFMAs it
+            // does not depend on.
             f32x16 s, dp;
 #pragma unroll
             for (int i = 0; i < 16; ++i) { s[i] = 0.0f; dp[i] = 0.0f; }
-            bf16x8 a[8], c[8];
+#define LRSA_DQ_OPND(n)                                                                                      \
+    ((n) < 8 ? read_rows_o(sK, lo, kb * 32, (n)) : (n) < 16 ? read_rows_o(sV, lo, kb * 32, (n) - 8)           \
+             : read_cols_o(sK, lo, kb * 32 + ((n) >= 20 ? 16 : 0), (n) & 3))
+            bf16x8 a[DQ_PF];
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk) a[kk] = read_rows_o(sK, lo, kb * 32, kk);
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                s = mfma32(a[kk], qf[kk], s);
-                c[kk] = read_rows_o(sV, lo, kb * 32, kk);
-            }
-            bf16x8 ka[4], kc[4];
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                dp = mfma32(c[kk], gf[kk], dp);
-                if (kk < 4) ka[kk] = read_cols_o(sK, lo, kb * 32, kk);
-            }
+            for (int n = 0; n < DQ_PF; ++n) a[n] = LRSA_DQ_OPND(n);
             const float neg_l = -lse2;
+            bf16x8 dsf0, dsf1;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float pr = fast_exp2(__builtin_fmaf(s[i], c2, neg_l));
-                if (MASK) {
-                    const int j = j0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-                    pr = j <= lim ? pr : 0.0f;
+            for (int n = 0; n < 24; ++n) {
+                if (n < 8) s = mfma32(a[n % DQ_PF], qf[n], s);
+                else if (n < 16) dp = mfma32(a[n % DQ_PF], gf[n - 8], dp);
+                else if (n < 20) dq[n - 16] = mfma32(a[n % DQ_PF], dsf0, dq[n - 16]);
+                else dq[n - 20] = mfma32(a[n % DQ_PF], dsf1, dq[n - 20]);
+                if (n + DQ_PF < 24) a[n % DQ_PF] = LRSA_DQ_OPND(n + DQ_PF);
+                if (n >= 8 && n < 16) {
+#pragma unroll
+                    for (int i = 2 * (n - 8); i < 2 * (n - 8) + 2; ++i) {
+                        float pr = fast_exp2(__builtin_fmaf(s[i], c2, neg_l));
+                        if (MASK) {
+                            const int j = j0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+                            pr = j <= lim ? pr : 0.0f;
+                        }
+                        s[i] = pr;
+                    }
                 }
-                s[i] = pr * (dp[i] - Dq);
-            }
-            {
-                const bf16x8 dsf = pack8(s, 0);
+                if (n == 15) {
 #pragma unroll
-                for (int db = 0; db < 4; ++db) {
-                    dq[db] = mfma32(ka[db], dsf, dq[db]);
-                    kc[db] = read_cols_o(sK, lo, kb * 32 + 16, db);
+                    for (int i = 0; i < 16; ++i) s[i] *= dp[i] - Dq;
+                    dsf0 = pack8(s, 0);
+                    dsf1 = pack8(s, 8);
                 }
             }
-            {
-                const bf16x8 dsf = pack8(s, 8);
-#pragma unroll
-                for (int db = 0; db < 4; ++db) dq[db] = mfma32(kc[db], dsf, dq[db]);
-            }
+#undef LRSA_DQ_OPND
         }
     }
 }
