@@ -159,6 +159,76 @@ __device__ __forceinline__ void dq_tile(const unsigned char* sK, const unsigned 
     }
 }
 
+// A tile all of whose 64 keys every query of the wave sees: both 32-key halves as ONE stream of 48 MFMAs,
+//   S0 | dA0 (+ exp of half 0) | S1 (+ dS of half 0) | dA1 (+ exp of half 1) | dQ0 (+ dS of half 1) | dQ1,
+// so that every piece of vector work sits beside MFMAs it does not depend on.  LDS operands are read DQ_PF ahead.
+__device__ __forceinline__ void dq_tile_full(const unsigned char* sK, const unsigned char* sV, const bf16x8 (&qf)[8],
+                                             const bf16x8 (&gf)[8], const LaneOffs& lo_in, f32x16 (&dq)[4], float c2,
+                                             float lse2, float Dq) {
+    // the two offset registers are made opaque here so that the XORed per-block offsets are formed next
+    // to each read (one vector op) instead of being kept in registers across the whole walk
+    LaneOffs lo = lo_in;
+    asm volatile("" : "+v"(lo.row), "+v"(lo.col));
+    f32x16 s0, dp0, s1, dp1, zero;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
+#define LRSA_DQ_OPND(n)                                                                                        \
+    ((n) < 8 ? read_rows_o(sK, lo, 0, (n)) : (n) < 16 ? read_rows_o(sV, lo, 0, (n) - 8)                         \
+     : (n) < 24 ? read_rows_o(sK, lo, 32, (n) - 16) : (n) < 32 ? read_rows_o(sV, lo, 32, (n) - 24)              \
+     : read_cols_o(sK, lo, ((n) - 32) / 4 * 16, (n) & 3))
+    bf16x8 a[DQ_PF];
+#pragma unroll
+    for (int n = 0; n < DQ_PF; ++n) a[n] = LRSA_DQ_OPND(n);
+    const float neg_l = -lse2;
+    bf16x8 dsf[4];   // dS of keys 0-15, 16-31, 32-47, 48-63
+    // six groups of eight MFMAs (separate loops: each unrolls fully, so every array index is a constant)
+#define LRSA_DQ_NEXT(n) if ((n) + DQ_PF < 48) a[(n) % DQ_PF] = LRSA_DQ_OPND((n) + DQ_PF)
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        s0 = mfma32(a[k % DQ_PF], qf[k], k == 0 ? zero : s0);
+        LRSA_DQ_NEXT(k);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        dp0 = mfma32(a[(8 + k) % DQ_PF], gf[k], k == 0 ? zero : dp0);
+        LRSA_DQ_NEXT(8 + k);
+#pragma unroll
+        for (int i = 2 * k; i < 2 * k + 2; ++i) s0[i] = fast_exp2(__builtin_fmaf(s0[i], c2, neg_l));
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        s1 = mfma32(a[(16 + k) % DQ_PF], qf[k], k == 0 ? zero : s1);
+        LRSA_DQ_NEXT(16 + k);
+#pragma unroll
+        for (int i = 2 * k; i < 2 * k + 2; ++i) s0[i] *= dp0[i] - Dq;
+    }
+    dsf[0] = pack8(s0, 0);
+    dsf[1] = pack8(s0, 8);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        dp1 = mfma32(a[(24 + k) % DQ_PF], gf[k], k == 0 ? zero : dp1);
+        LRSA_DQ_NEXT(24 + k);
+#pragma unroll
+        for (int i = 2 * k; i < 2 * k + 2; ++i) s1[i] = fast_exp2(__builtin_fmaf(s1[i], c2, neg_l));
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        dq[k & 3] = mfma32(a[(32 + k) % DQ_PF], dsf[k >> 2], dq[k & 3]);
+        LRSA_DQ_NEXT(32 + k);
+#pragma unroll
+        for (int i = 2 * k; i < 2 * k + 2; ++i) s1[i] *= dp1[i] - Dq;
+    }
+    dsf[2] = pack8(s1, 0);
+    dsf[3] = pack8(s1, 8);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        dq[k & 3] = mfma32(a[(40 + k) % DQ_PF], dsf[2 + (k >> 2)], dq[k & 3]);
+        LRSA_DQ_NEXT(40 + k);
+    }
+#undef LRSA_DQ_NEXT
+#undef LRSA_DQ_OPND
+}
+
 // GH query heads of one KV group share the workgroup (8 waves = GH heads x 256/GH queries), as in the forward.
 // COMPACT: the rows of the gather list come from the condensed cache Kc, Vc (contiguous), no index is read.
 template <int GH, bool COMPACT>
@@ -256,7 +326,7 @@ __global__ __launch_bounds__(DQ_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t* 
     {                                                                                                           \
         const int j0 = (j0_);                                                                                   \
         if (j0 + DQ_BN - 1 <= wave_lim_min)                                                                     \
-            dq_tile<false>(sK, sV, qf, gf, lo, dq, j0, lim, wave_lim_max, c2, lse2, Dq, lane);                  \
+            dq_tile_full(sK, sV, qf, gf, lo, dq, c2, lse2, Dq);                                                 \
         else if (j0 <= wave_lim_max)                                                                            \
             dq_tile<true>(sK, sV, qf, gf, lo, dq, j0, lim, wave_lim_max, c2, lse2, Dq, lane);                   \
     }
