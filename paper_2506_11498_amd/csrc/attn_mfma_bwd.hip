@@ -21,19 +21,13 @@
 namespace lrsa {
 
 constexpr int BWD_THREADS = 256;
-#ifndef LRSA_KV_WAVES
-#define LRSA_KV_WAVES 8
-#endif
-#ifndef LRSA_KV_NB
-#define LRSA_KV_NB 1
-#endif
-constexpr int KV_WAVES = LRSA_KV_WAVES;   // waves per workgroup of the key-outer kernel
+constexpr int KV_WAVES = 8;              // waves per workgroup of the key-outer kernel (two per SIMD)
 constexpr int KV_THREADS = 64 * KV_WAVES;
 constexpr int DQ_BN = 64;
 constexpr int DQ_PF = 4;                 // LDS operands of the query-outer kernel are read this many MFMAs ahead
 constexpr int DQ_WAVES = 8;              // waves per workgroup of the query-outer kernel (two per SIMD)
 constexpr int DQ_THREADS = 64 * DQ_WAVES;
-constexpr int KV_NB = LRSA_KV_NB;               // 32-key blocks per wave
+constexpr int KV_NB = 1;                        // 32-key blocks per wave (2 needs one wave per SIMD: measured slower)
 constexpr int KV_BK = 32 * KV_NB * KV_WAVES;   // keys per workgroup
 constexpr int KV_BQ = 32;   // query rows per MFMA sub-step
 constexpr int KV_SUB = 2;   // sub-steps per pipeline step (one LDS stage, one barrier)

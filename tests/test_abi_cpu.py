@@ -109,3 +109,34 @@ def test_product_package_does_not_import_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"^\s*(from|import)\s+oracle\b", text, flags=re.M), f
                 assert "liblrsa_oracle" not in text and "lrsa_rows" not in text and "lrsa_ref" not in text, f
+
+
+def test_inference_cache_calls_validate_on_the_host():
+    """lrsa_cache_compress computes the new length and chunk count on the host and launches nothing when the
+    tail is short; bad lengths, local_prev != 1 and null outputs fail before any GPU work."""
+    L = lrsa.lib()
+    p = _params(n=4096, sink=16, lag=256, topk=64)          # seq = capacity of the cache
+    new_len, new_done = ctypes.c_int32(-1), ctypes.c_int32(-1)
+    out = (ctypes.byref(new_len), ctypes.byref(new_done))
+    # tail of 2*lag - 1 rows: nothing to do, no pointer is touched
+    assert L.lrsa_cache_compress(ctypes.byref(p), None, None, None, 16 + 511, 0, *out, None) == 0
+    assert (new_len.value, new_done.value) == (16 + 511, 0)
+    # three compressed chunks and a tail of lag + 5 rows: still nothing to do
+    assert L.lrsa_cache_compress(ctypes.byref(p), None, None, None, 16 + 3 * 64 + 261, 3, *out, None) == 0
+    assert (new_len.value, new_done.value) == (16 + 3 * 64 + 261, 3)
+    # a full tail needs the buffers
+    assert L.lrsa_cache_compress(ctypes.byref(p), None, None, None, 16 + 512, 0, *out, None) == -1
+    assert (new_len.value, new_done.value) == (16 + 64 + 256, 1)          # the arithmetic is done first
+    assert L.lrsa_cache_compress(ctypes.byref(p), None, None, None, 5000, 0, *out, None) == -1    # beyond the capacity
+    assert L.lrsa_cache_compress(ctypes.byref(p), None, None, None, 16 + 64 + 10, 1, *out, None) == -1   # too short for 1 chunk
+    assert L.lrsa_cache_compress(ctypes.byref(p), None, None, None, 100, 0, None, None, None) == -1
+    p2 = _params(n=4096, sink=16, lag=256, topk=64, local_prev=2)
+    assert L.lrsa_cache_compress(ctypes.byref(p2), None, None, None, 16 + 512, 0, *out, None) == -2
+    # decode attention: length and pointers
+    assert L.lrsa_decode_attn(ctypes.byref(p), None, None, None, 0, None, None, None, 0, None) == -1
+    assert L.lrsa_decode_attn(ctypes.byref(p), None, None, None, 10, None, None, None, 0, None) == -1
+    assert b"NULL" in L.lrsa_last_error()
+    assert lrsa.workspace_bytes(p, binding.WS_DECODE_ATTN) > 0
+    # the condensed-cache variant asks for a larger attention workspace
+    pc = _params(impl=binding.IMPL_COMPACT)
+    assert lrsa.workspace_bytes(pc, binding.WS_ATTN_FWD) > lrsa.workspace_bytes(_params(), binding.WS_ATTN_FWD)
