@@ -246,14 +246,26 @@ def full_workload_parity(name, kv_heads, batch=0, n_rows=None, n_cols=None, late
     Kf, Vf = x["K"].float().numpy(), x["V"].float().numpy()
     sc_ref = ref.score(Kf, Vf, w.S, w.L)
     idx_ref = ref.select(sc_ref, w.S, w.L, w.K)
-    p, score, idx = run_score_select(w, xd)
+    # the calls as bench.py makes them: one launch for score + select, preallocated outputs, one workspace
+    # of the largest size shared by all calls
+    p = params(w, xd)
+    Ns = lrsa.num_scored_chunks(p)
+    ws = torch.empty(max(max(lrsa.workspace_bytes(p, k) for k in range(4)), 256), dtype=torch.uint8, device=DEV)
+    score = torch.empty((w.B, w.Hkv, Ns, w.L), dtype=torch.float32, device=DEV)
+    idx = torch.empty((w.B, w.Hkv, Ns, w.K), dtype=torch.int32, device=DEV)
+    lrsa.lrsa_score_select(p, xd["K"], xd["V"], score, idx, ws)
+    score2 = lrsa.lrsa_score(p, xd["K"], xd["V"], None, ws)
+    assert torch.equal(score2, score) and torch.equal(lrsa.lrsa_select(p, score2, None, ws), idx)
     assert np.allclose(to_np(score), sc_ref, rtol=2e-5, atol=1e-9)
     assert np.array_equal(lrsa.lrsa_select(p, torch.from_numpy(sc_ref).to(DEV)).cpu().numpy(), idx_ref)
     exact = check_selection_in_tie_window(w, idx.cpu().numpy(), idx_ref, sc_ref)
     print(f"{name}: end-to-end selection exact on {100 * exact:.2f}% of windows")
     idx_dev = torch.from_numpy(idx_ref).to(DEV)
-    O, lse = lrsa.lrsa_attn_fwd(p, xd["Q"], xd["K"], xd["V"], idx_dev)
-    dQ, dK, dV = lrsa.lrsa_attn_bwd(p, xd["Q"], xd["K"], xd["V"], O, xd["dO"], lse, idx_dev)
+    O, dQ = torch.empty_like(xd["Q"]), torch.empty_like(xd["Q"])
+    lse = torch.empty((w.B, w.Hq, w.n), dtype=torch.float32, device=DEV)
+    dK, dV = torch.empty_like(xd["K"]), torch.empty_like(xd["K"])
+    lrsa.lrsa_attn_fwd(p, xd["Q"], xd["K"], xd["V"], idx_dev, O, lse, ws)
+    lrsa.lrsa_attn_bwd(p, xd["Q"], xd["K"], xd["V"], O, xd["dO"], lse, idx_dev, dQ, dK, dV, ws)
     torch.cuda.synchronize()
     t = tol(w.dtype)
     rng = np.random.default_rng(seed)
