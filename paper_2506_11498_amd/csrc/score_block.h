@@ -22,6 +22,16 @@ struct ScoreLds {
 // between rows; L <= FUSED_MAX_L rows each.  On return sh.sig[0][r] holds the score of row r (also written
 // to out[r] when out is not null); all threads have passed a barrier after the last LDS write they depend on
 // only for their own r = tid, tid + 1024, ... -- callers that read other rows synchronise first.
+// sum over the 16 lanes that share a row, every lane gets the total: four rotations inside the row of 16
+// (data-parallel primitive, no LDS round trip)
+__device__ __forceinline__ float row16_sum(float v) {
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xf, 0xf, false));   // row_ror:8
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x124, 0xf, 0xf, false));   // row_ror:4
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x122, 0xf, 0xf, false));   // row_ror:2
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x121, 0xf, 0xf, false));   // row_ror:1
+    return v;
+}
+
 template <typename T>
 __device__ __forceinline__ void score_chunk_block(int L, int d, int ddof, const T* __restrict__ Kcur,
                                                   const T* __restrict__ Kref, const T* __restrict__ Vcur,
@@ -33,6 +43,9 @@ __device__ __forceinline__ void score_chunk_block(int L, int d, int ddof, const 
     const int rpp = FUSED_THREADS / lpr;      // rows per pass
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = tid % lpr, rg = tid / lpr;
+    const bool rows16 = lpr == 16;                  // 256-byte rows: the channel sums stay inside a row of 16 lanes
+    const float inv_d = 1.0f / float(d);            // exact: head_dim is a power of two
+    const float inv_dof = 1.0f / float(d - ddof);
     // ---- phase 1
     {
         float mn[2][VEC], mx[2][VEC];
@@ -115,27 +128,37 @@ __device__ __forceinline__ void score_chunk_block(int L, int d, int ddof, const 
                 }
                 sm4[j] = acc;
             }
-            for (int o = lpr >> 1; o > 0; o >>= 1)
+            if (rows16) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) sm4[j] += __shfl_xor(sm4[j], o, 64);
+                for (int j = 0; j < 4; ++j) sm4[j] = row16_sum(sm4[j]);
+            } else {
+                for (int o = lpr >> 1; o > 0; o >>= 1)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) sm4[j] += __shfl_xor(sm4[j], o, 64);
+            }
             float var4[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const float m = sm4[j] / float(d);
+                const float m = sm4[j] * inv_d;
                 float acc = 0.0f;
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) { const float dd = x[j][i] - m; acc += dd * dd; }
                 var4[j] = acc;
             }
-            for (int o = lpr >> 1; o > 0; o >>= 1)
+            if (rows16) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) var4[j] += __shfl_xor(var4[j], o, 64);
+                for (int j = 0; j < 4; ++j) var4[j] = row16_sum(var4[j]);
+            } else {
+                for (int o = lpr >> 1; o > 0; o >>= 1)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) var4[j] += __shfl_xor(var4[j], o, 64);
+            }
             if (sub == 0) {
-                sh.sig[0][r] = sqrtf(var4[0] / float(d - ddof));
-                sh.sig[1][r] = sqrtf(var4[2] / float(d - ddof));
+                sh.sig[0][r] = sqrtf(var4[0] * inv_dof);
+                sh.sig[1][r] = sqrtf(var4[2] * inv_dof);
                 if (has2) {
-                    sh.sig[0][r2] = sqrtf(var4[1] / float(d - ddof));
-                    sh.sig[1][r2] = sqrtf(var4[3] / float(d - ddof));
+                    sh.sig[0][r2] = sqrtf(var4[1] * inv_dof);
+                    sh.sig[1][r2] = sqrtf(var4[3] * inv_dof);
                 }
             }
         }
