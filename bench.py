@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the LRSA hot path on one MI355X.
 
-A step is one pass of the whole path -- lrsa_score, lrsa_select, lrsa_attn_fwd, lrsa_attn_bwd --
-over one synthetic batch that is already resident in HBM.  The workload is the 32K-token GQA
+A step is one pass of the whole path -- scoring and selection (lrsa_score_select: both in one launch; the
+two separate calls with --separate-score-select), lrsa_attn_fwd, lrsa_attn_bwd -- over one synthetic batch
+that is already resident in HBM.  The workload is the 32K-token GQA
 config ("C4": B1, 32 query / 8 KV heads, d 128, n 32768, L 1024, K 256, S 64, bf16) unless
 --workload says otherwise.  Prints ONE JSON line:
 

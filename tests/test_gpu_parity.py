@@ -315,3 +315,49 @@ def test_workload_C6_paper_training_shape():
 
 def test_workload_C5_stress_128k():
     full_workload_parity("C5", kv_heads=[1, 6], n_rows=64, n_cols=8, late_cols_only=True)
+
+
+def test_whole_path_replays_from_a_captured_graph():
+    """The four calls enqueue on the caller's stream, allocate nothing and never synchronise, so a step can be
+    captured once and replayed: every replay (with fresh input contents, eager work in between) must give the
+    bits of the eager run on the same inputs."""
+    w = inputs.small_workload(n=16 + 6 * 64 + 40, L=64, S=16, K=16, d=128, Hq=8, Hkv=2, B=2, dtype="bf16")
+    x = {k: v.to(DEV) for k, v in inputs.make_inputs(w).items()}
+    p = params(w, x)
+    Ns = lrsa.num_scored_chunks(p)
+    ws = torch.empty(max(max(lrsa.workspace_bytes(p, k) for k in range(4)), 256), dtype=torch.uint8, device=DEV)
+    score = torch.empty((w.B, w.Hkv, Ns, w.L), dtype=torch.float32, device=DEV)
+    idx = torch.empty((w.B, w.Hkv, Ns, w.K), dtype=torch.int32, device=DEV)
+    O, dQ = torch.empty_like(x["Q"]), torch.empty_like(x["Q"])
+    lse = torch.empty((w.B, w.Hq, w.n), dtype=torch.float32, device=DEV)
+    dK, dV = torch.empty_like(x["K"]), torch.empty_like(x["K"])
+    outs = (score, idx, O, lse, dQ, dK, dV)
+
+    def step():
+        lrsa.lrsa_score_select(p, x["K"], x["V"], score, idx, ws)
+        lrsa.lrsa_attn_fwd(p, x["Q"], x["K"], x["V"], idx, O, lse, ws)
+        lrsa.lrsa_attn_bwd(p, x["Q"], x["K"], x["V"], O, x["dO"], lse, idx, dQ, dK, dV, ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                   # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    gen = torch.Generator(device=DEV).manual_seed(7)
+    for rep in range(3):
+        for k in ("Q", "K", "V", "dO"):          # new contents in the same buffers
+            x[k].copy_(torch.randn(x[k].shape, generator=gen, device=DEV).to(x[k].dtype))
+        step()
+        torch.cuda.synchronize()
+        want = [t.clone() for t in outs]
+        for t in outs:
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(outs, want):
+            assert torch.equal(a, b), f"replay {rep} differs from the eager run"
