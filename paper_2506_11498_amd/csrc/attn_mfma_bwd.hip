@@ -388,8 +388,13 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
     const int g = lane >> 5;
     // the two offset registers are made opaque here so that the XORed per-block offsets are formed next
     // to each read (one VALU op) instead of being kept in sixteen registers across the whole walk
-    LaneOffs lo = lo_in;
-    asm volatile("" : "+v"(lo.row), "+v"(lo.col));
+    // The lane's offsets with the addresses of the three tiles folded in (the tiles start on 256-byte
+    // boundaries): one add per tile and sub-step, then one XOR per read.  The registers are made opaque so
+    // that the XORed per-block addresses are formed next to each read instead of being kept across the walk.
+    unsigned aQr = lo_in.row + lds_addr(sQ) + rowbase * TILE_ROW_BYTES, aQc = lo_in.col + lds_addr(sQ) + rowbase * TILE_ROW_BYTES;
+    unsigned aGr = lo_in.row + lds_addr(sG) + rowbase * TILE_ROW_BYTES, aGc = lo_in.col + lds_addr(sG) + rowbase * TILE_ROW_BYTES;
+    unsigned aVr = lo_in.row + lds_addr(sVw);
+    asm volatile("" : "+v"(aQr), "+v"(aQc), "+v"(aGr), "+v"(aGc), "+v"(aVr));
     // Four MFMA groups: S, dA, dV, dK (8 MFMAs per 32-key block each).  The vector work between them is
     // written next to MFMAs it does not depend on -- exp(S) beside the dA group, dS beside the dV group --
     // so that one wave keeps both pipes busy.  Operands are read two ahead of the MFMAs that consume them;
@@ -400,13 +405,13 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
     for (int nb = 0; nb < KV_NB; ++nb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) { s[nb][i] = 0.0f; dp[nb][i] = 0.0f; }
-    a[0] = read_rows_o(sQ, lo, rowbase, 0);
-    a[1] = read_rows_o(sQ, lo, rowbase, 1);
+    a[0] = read_rows_a(aQr, 0);
+    a[1] = read_rows_a(aQr, 1);
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
 #pragma unroll
         for (int nb = 0; nb < KV_NB; ++nb) s[nb] = mfma32(a[kk & 1], kf[nb][kk], s[nb]);
-        a[kk & 1] = kk < 6 ? read_rows_o(sQ, lo, rowbase, kk + 2) : read_rows_o(sG, lo, rowbase, kk - 6);
+        a[kk & 1] = kk < 6 ? read_rows_a(aQr, kk + 2) : read_rows_a(aGr, kk - 6);
     }
     // mask bounds: row rho = 8*a4 + 4g + r of the step is visible to key block nb iff mlo[nb] <= 8*a4 + r < mhi
     const int mhi = (tb - r0) - 4 * g;
@@ -419,17 +424,17 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
     // padding keys pay for the mask (wave-uniform flag).
     bf16x8 vb[KV_NB][2];
 #pragma unroll
-    for (int nb = 0; nb < KV_NB; ++nb) vb[nb][0] = read_rows_o(sVw, lo, nb * 32, 0);
+    for (int nb = 0; nb < KV_NB; ++nb) vb[nb][0] = read_rows_a(aVr + nb * 32 * TILE_ROW_BYTES, 0);
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
 #pragma unroll
         for (int nb = 0; nb < KV_NB; ++nb) {
-            if (kk + 1 < 8) vb[nb][(kk + 1) & 1] = read_rows_o(sVw, lo, nb * 32, kk + 1);
+            if (kk + 1 < 8) vb[nb][(kk + 1) & 1] = read_rows_a(aVr + nb * 32 * TILE_ROW_BYTES, kk + 1);
             dp[nb] = mfma32(a[kk & 1], vb[nb][kk & 1], dp[nb]);
         }
         // next operands: the rest of the dO rows, then the first transposed dO operands
-        if (kk < 6) a[kk & 1] = read_rows_o(sG, lo, rowbase, kk + 2);
-        else a[kk & 1] = read_cols_o(sG, lo, rowbase, kk - 6);
+        if (kk < 6) a[kk & 1] = read_rows_a(aGr, kk + 2);
+        else a[kk & 1] = read_cols_a(aGc, 0, kk - 6);
         if ((kk & 1) == 0) {
             const int a4 = kk >> 1;
             const f32x4 l4 = *reinterpret_cast<const f32x4*>(sLD + rowbase + 8 * a4 + 4 * g);
@@ -456,7 +461,7 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
     for (int nb = 0; nb < KV_NB; ++nb) { pf[nb][0] = pack8(s[nb], 0); pf[nb][1] = pack8(s[nb], 8); }
     // dV^T += dO^T A (rows 0-15 blocks 0..3, rows 16-31 blocks 0..3) with dS = A * (dA - D) beside it,
     // then dK^T += Q^T dS in the same order
-#define LRSA_OPND(n) ((n) < 8 ? read_cols_o(sG, lo, rowbase + ((n) >> 2) * 16, (n) & 3) : read_cols_o(sQ, lo, rowbase + (((n) - 8) >> 2) * 16, (n) & 3))
+#define LRSA_OPND(n) ((n) < 8 ? read_cols_a(aGc, ((n) >> 2) * 16, (n) & 3) : read_cols_a(aQc, (((n) - 8) >> 2) * 16, (n) & 3))
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
 #pragma unroll
@@ -500,10 +505,10 @@ struct KvLds {
 };
 // one set of arrays for both instantiations of the body (a template would get a set each)
 __device__ __forceinline__ KvLds kv_lds() {
-    __shared__ __attribute__((aligned(16))) unsigned char sQ0[KV_ROWS * TILE_ROW_BYTES], sQ1[KV_ROWS * TILE_ROW_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char sG0[KV_ROWS * TILE_ROW_BYTES], sG1[KV_ROWS * TILE_ROW_BYTES];
+    __shared__ __attribute__((aligned(256))) unsigned char sQ0[KV_ROWS * TILE_ROW_BYTES], sQ1[KV_ROWS * TILE_ROW_BYTES];
+    __shared__ __attribute__((aligned(256))) unsigned char sG0[KV_ROWS * TILE_ROW_BYTES], sG1[KV_ROWS * TILE_ROW_BYTES];
     __shared__ __attribute__((aligned(16))) float sL0[KV_WAVES * 2 * KV_ROWS], sL1[KV_WAVES * 2 * KV_ROWS];
-    __shared__ __attribute__((aligned(16))) unsigned char sVk[KV_BK * TILE_ROW_BYTES];
+    __shared__ __attribute__((aligned(256))) unsigned char sVk[KV_BK * TILE_ROW_BYTES];
     return KvLds{sQ0, sQ1, sG0, sG1, sL0, sL1, sVk};
 }
 

@@ -90,6 +90,27 @@ __device__ __forceinline__ bf16x8 read_cols_o(const unsigned char* tile, const L
     return u.v;
 }
 
+// The same two reads with the tile's LDS address already folded into the lane's offset register (one add
+// per tile instead of one per read): valid when the tile starts on a 256-byte boundary, because XORing a
+// constant below 256 then commutes with adding the base.  rows16 is a compile-time row offset (multiple of 16).
+typedef bf16x8 __attribute__((address_space(3))) * lds_bf16x8_ptr;
+__device__ __forceinline__ unsigned lds_addr(const void* p) {
+    return (unsigned)(size_t)(__attribute__((address_space(3))) void*)p;
+}
+__device__ __forceinline__ bf16x8 read_rows_a(unsigned arow, int kk) {
+    return *(lds_bf16x8_ptr)(size_t)(arow ^ unsigned(kk << 5));
+}
+__device__ __forceinline__ bf16x8 read_cols_a(unsigned acol, int rows16, int db) {
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(size_t)((acol ^ unsigned(db << 6)) + rows16 * TILE_ROW_BYTES));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_ptr)(size_t)((acol ^ unsigned((db << 6) | 32)) + (rows16 + 8) * TILE_ROW_BYTES));
+    union { s16x4 h[2]; bf16x8 v; } u;
+    u.h[0] = lo;
+    u.h[1] = hi;
+    return u.v;
+}
+
 // registers i0 .. i0+7 of a C-layout accumulator as a bf16 operand
 __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int i0) {
     f32x8 t;
