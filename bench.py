@@ -178,7 +178,7 @@ def main():
     ms_score = stage(["k_score_select_fused", "k_score_fused", "k_minmaxT", "k_sigmaT", "k_softmax"])
     ms_select = stage(["k_select"])
     ms_fwd = stage(["k_fwd_mfma", "k_fwd_genericT"])      # k_compact_kv runs in both calls: counted below
-    ms_bwd = stage(["k_bwd_rowdot", "k_bwd_dq", "k_bwd_dkv", "k_bwd_dkv_reduce", "k_bwd_dq_genericT", "k_bwd_dkv_genericT",
+    ms_bwd = stage(["k_bwd_dq", "k_bwd_dkv", "k_bwd_dkv_reduce", "k_bwd_dq_genericT", "k_bwd_dkv_genericT",
                     "k_compact_kv"])
     ss_bytes = score_bytes + 4 * w.B * w.Hkv * Ns * w.K     # K and V read once, scores and idx written once
     ss_gbps = ss_bytes / max(ms_score + ms_select, 1e-9) / 1e6

@@ -2,10 +2,10 @@
 // the mask constant:  A = exp(scale Q K^T + M - lse), dV = A^T dO, dA = dO V^T,
 // D = rowsum(dO * O), dS = A * (dA - D), dQ = scale dS K, dK = scale dS^T Q.
 //
-// Deterministic, no atomics.  Four launches on one stream:
-//   k_bwd_rowdot      D[b,hq,t] = dO[t] . O[t], and lse in log2 units
+// Deterministic, no atomics.  Three launches on one stream:
 //   k_bwd_dq          query-outer: a workgroup owns 256 (head, query) rows of one KV group and walks their
-//                     key stream exactly like the forward (gather list, then the local window), recomputing A
+//                     key stream exactly like the forward (gather list, then the local window), recomputing A;
+//                     it also leaves D[b,hq,t] = dO[t] . O[t] and lse in log2 units in the workspace
 //   k_bwd_dkv         key-outer, two kinds of workgroups in one launch.  GATHER: 256 consecutive entries of one
 //                     KV head's gather list (sink ++ survivors) x one slice of query chunks -> fp32 partial
 //                     dK, dV rows in the workspace.  WINDOW: 256 consecutive positions x the queries that see
@@ -20,7 +20,6 @@
 
 namespace lrsa {
 
-constexpr int BWD_THREADS = 256;
 constexpr int KV_WAVES = 8;              // waves per workgroup of the key-outer kernel (two per SIMD)
 constexpr int KV_THREADS = 64 * KV_WAVES;
 constexpr int DQ_BN = 64;
@@ -69,34 +68,6 @@ static BwdPlan make_plan(const Dims& D) {
 }
 
 size_t attn_bwd_mfma_ws_bytes(const Dims& D) { return make_plan(D).bytes; }
-
-// ------------------------------------------------------------------------------------ D = rowsum(dO * O)
-__global__ __launch_bounds__(BWD_THREADS) void k_bwd_rowdot(Dims D, const bf16_t* __restrict__ O,
-                                                             const bf16_t* __restrict__ dO,
-                                                             const float* __restrict__ lse,
-                                                             float* __restrict__ Dsum, float* __restrict__ lse2) {
-    // 16 lanes per row, 16 rows per workgroup
-    const int sub = threadIdx.x & 15;
-    const int64_t row = int64_t(blockIdx.x) * 16 + (threadIdx.x >> 4);
-    const int64_t nrows = int64_t(D.B) * D.Hq * D.n;
-    float acc = 0.0f;
-    if (row < nrows) {
-        const int t = int(row % D.n);
-        const int hq = int((row / D.n) % D.Hq), b = int(row / (int64_t(D.n) * D.Hq));
-        const int64_t off = b * D.qs[0] + hq * D.qs[1] + int64_t(t) * D.qs[2] + sub * 8;
-        float a[8], c[8];
-        Elem<bf16_t>::load(O + off, a);
-        Elem<bf16_t>::load(dO + off, c);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc += a[i] * c[i];
-    }
-#pragma unroll
-    for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-    if (row < nrows && sub == 0) {
-        Dsum[row] = acc;
-        lse2[row] = lse[row] * 1.4426950408889634f;   // the main kernels work in log2 units
-    }
-}
 
 // ------------------------------------------------------------------------------------ dQ
 // One 64-key tile for one wave: per 32 keys S^T and dA^T, then dS^T, then dQ^T += K^T dS^T.
@@ -229,9 +200,10 @@ template <int GH, bool COMPACT>
 __global__ __launch_bounds__(DQ_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t* __restrict__ Q,
                                                            const bf16_t* __restrict__ K,
                                                            const bf16_t* __restrict__ V,
+                                                           const bf16_t* __restrict__ O,
                                                            const bf16_t* __restrict__ dO,
                                                            const float* __restrict__ lse,
-                                                           const float* __restrict__ Dsum,
+                                                           float* __restrict__ Dsum, float* __restrict__ lse2_out,
                                                            const int32_t* __restrict__ idx,
                                                            const bf16_t* __restrict__ Kc,
                                                            const bf16_t* __restrict__ Vc,
@@ -279,9 +251,19 @@ __global__ __launch_bounds__(DQ_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t* 
         qf[kk] = *reinterpret_cast<const bf16x8*>(Q + qoff + kk * 16 + g * 8);
         gf[kk] = *reinterpret_cast<const bf16x8*>(dO + qoff + kk * 16 + g * 8);
     }
+    // D = rowsum(dO * O) of this lane's row and its lse in log2 units: used here and, through the workspace,
+    // by the key-outer kernel that runs after this one (every (head, query) row belongs to exactly one wave)
     const int64_t rowid = (int64_t(b) * D.Hq + hq) * D.n + tq_ld;
-    const float lse2 = lse[rowid];   // already in log2 units
-    const float Dq = Dsum[rowid];
+    const float lse2 = lse[rowid] * 1.4426950408889634f;
+    float Dq = 0.0f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        const bf16x8 o8 = *reinterpret_cast<const bf16x8*>(O + qoff + kk * 16 + g * 8);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) Dq = __builtin_fmaf(float(o8[i]), float(gf[kk][i]), Dq);
+    }
+    Dq += __shfl_xor(Dq, 32, 64);
+    if (tq <= t_last && g == 0) { Dsum[rowid] = Dq; lse2_out[rowid] = lse2; }
     const int lim = ng + tq - cs;
     const int wave_lim_max = ng + min(t0 + wq * 32 + 31, t_last) - cs;
 
@@ -816,10 +798,6 @@ hipError_t launch_attn_bwd_mfma(const Dims& D, const void* Q, const void* K, con
     const bf16_t *q = (const bf16_t*)Q, *k = (const bf16_t*)K, *v = (const bf16_t*)V, *o = (const bf16_t*)O,
                  *g = (const bf16_t*)dO;
 
-    const int64_t nrows = int64_t(D.B) * D.Hq * D.n;
-    LRSA_TIMED_LAUNCH("k_bwd_rowdot", st, k_bwd_rowdot, dim3((unsigned)((nrows + 15) / 16)), dim3(BWD_THREADS), 0, st, D, o, g, lse,
-                      Dsum, lse2);
-
     {
         const int gh = heads_per_wg(D);
         const QTileMap M = make_qtile_map(D, gh, DQ_WAVES);
@@ -833,8 +811,8 @@ hipError_t launch_attn_bwd_mfma(const Dims& D, const void* Q, const void* K, con
             if (e != hipSuccess) return e;
         }
 #define LRSA_DQ_LAUNCH(GH_, C_)                                                                                     \
-    LRSA_TIMED_LAUNCH("k_bwd_dq", st, (k_bwd_dq<GH_, C_>), dim3((unsigned)wgs), dim3(DQ_THREADS), 0, st, D, q, k, v, g, lse2, \
-                      Dsum, idx, kc, vc, (bf16_t*)dQ, M)
+    LRSA_TIMED_LAUNCH("k_bwd_dq", st, (k_bwd_dq<GH_, C_>), dim3((unsigned)wgs), dim3(DQ_THREADS), 0, st, D, q, k, v, o, g, lse, \
+                      Dsum, lse2, idx, kc, vc, (bf16_t*)dQ, M)
         if (wgs > 0) {
             if (gh == 4) { if (compact) LRSA_DQ_LAUNCH(4, true); else LRSA_DQ_LAUNCH(4, false); }
             else if (gh == 2) { if (compact) LRSA_DQ_LAUNCH(2, true); else LRSA_DQ_LAUNCH(2, false); }
