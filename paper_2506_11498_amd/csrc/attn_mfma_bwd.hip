@@ -55,6 +55,11 @@ static BwdPlan make_plan(const Dims& D) {
     const int min_qch = (D.nq + KV_MAX_SLICES - 1) / KV_MAX_SLICES;
     if (qch < min_qch) qch = min_qch;
     if (qch < 1) qch = 1;
+    // small problems: shorter slices (down to ~1024 query rows x G heads) until the gather workgroups -- about
+    // half of the (tile, slice) grid sees any query -- fill the chip twice
+    while (qch > min_qch && qch > 1 && (qch / 2) * int64_t(D.L) * D.G >= 1024 &&
+           int64_t(D.B) * D.Hkv * P.gtiles * ((D.nq + qch - 1) / qch) / 2 < 512)
+        qch /= 2;
     P.qch = int(qch);
     P.nsl = D.nq > 0 ? (D.nq + P.qch - 1) / P.qch : 0;
     P.off_lse2 = align256(size_t(D.B) * D.Hq * D.n * 4);
