@@ -167,8 +167,12 @@ def main():
         tpath = os.path.join(ROOT, "profiles", "traffic.json")
         if os.path.exists(tpath):
             traffic = json.load(open(tpath)).get(f"{dom}:{w.name}")
+        counters = None      # MFMA-busy fraction, clock and CU occupancy from the committed rocprofv3 --pmc run
+        cpath = os.path.join(ROOT, "profiles", "counters.json")
+        if os.path.exists(cpath):
+            counters = json.load(open(cpath)).get(f"{dom}:{w.name}")
         roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic, "avg_launch_ms": kern_ms[dom],
+                    "frac": ach / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic, "counters": counters, "avg_launch_ms": kern_ms[dom],
                     "algorithmic_flop_per_launch": kern_flops[dom]}
 
     def stage(names):
