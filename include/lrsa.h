@@ -121,8 +121,11 @@ int lrsa_score_select(const lrsa_params *p, const void *K, const void *V, float 
  * the keys u <= t that are in the sink, in the local window of t's chunk, or listed in idx;
  * lse[t] = log sum_u exp(scale q_t.k_u).  Query head hq reads KV head hq / G.
  *   Q     : [B, Hq, n, d_h] by q_stride; K, V: [B, Hkv, n, d_h] by kv_stride    (device, read)
- *   idx   : [B, Hkv, Ns, K] int32 as written by lrsa_select (ascending per chunk, inside the
- *           chunk); may be NULL when Ns == 0                                     (device, read)
+ *   idx   : [B, Hkv, Ns, K] int32 as written by lrsa_select; may be NULL when Ns == 0.
+ *           PRECONDITION (not checked on the device): row p holds K distinct positions of chunk p,
+ *           [S+pL, S+(p+1)L), strictly ascending.  Positions outside the sequence are read out of
+ *           bounds; a row that is not ascending sends gradients to wrong rows of dK, dV.
+ *                                                                                (device, read)
  *   O     : [B, Hq, n, d_h] by q_stride, dtype `dtype`                           (device, written)
  *   lse   : [B, Hq, n] fp32, contiguous                                          (device, written)
  * idx is an input, so any valid selection (for instance one computed elsewhere) can be used. */
@@ -141,8 +144,8 @@ int lrsa_attn_bwd(const lrsa_params *p, const void *Q, const void *K, const void
                   void *dQ, void *dK, void *dV, void *ws, size_t ws_bytes, void *stream);
 
 /* ---- inference-time LagKV cache (the setting of the paper's evaluation: the cache compressed lag window by
- * lag window while tokens are generated; "the KV cache is updated with the first chunk compressed and the
- * second chunk retained as a sliding window", Attention Filling 1).
+ * lag window while tokens are generated; Section 3.2, Attention Filling 1: once a second chunk is complete the
+ * chunk before it is cut down to its survivors and the newer one stays whole as the local window).
  *
  * Cache of one layer: Kc, Vc [B, Hkv, cap, d_h] by kv_stride with cap = p->seq; rows [0, len) valid, the same
  * len for every head: the sink rows, then topk rows per compressed chunk, then the uncompressed tail.

@@ -2,9 +2,9 @@
 
 The paper evaluates its models with the KV cache compressed by LagKV (evaluation tables, compression
 1x / 2x / 4x): the cache keeps the sink, and, lag window by lag window, only the top r*L tokens of a chunk
-once the chunk after it is complete ("the KV cache is updated with the first chunk compressed and the second
-chunk retained as a sliding window", Attention Filling 1; "select the top rL tokens to remain in the KV
-cache", text after Eq. 8).  This file writes that procedure out token by token for one KV head, and the
+once the chunk after it is complete (Section 3.2, Attention Filling 1: the older chunk is cut down to its
+survivors, the newer one stays whole as the local window; the survivors are the top r*L tokens by score,
+text after Eq. 8).  This file writes that procedure out token by token for one KV head, and the
 single-query attention over such a cache (Eq. 3 with nothing masked).
 
 It shares no code with the HIP path; it calls the training-time oracle's scoring formula

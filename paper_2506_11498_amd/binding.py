@@ -13,8 +13,7 @@ from typing import Optional, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# LRSA_LIB may point at another build of the same library (kernel experiments)
-LIB_PATH = os.environ.get("LRSA_LIB", os.path.join(_HERE, "liblrsa.so"))
+LIB_PATH = os.path.join(_HERE, "liblrsa.so")
 
 LRSA_F32, LRSA_BF16 = 0, 1
 IMPL_AUTO, IMPL_GENERIC, IMPL_COMPACT = 0, 1, 2
@@ -116,6 +115,41 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
+_TORCH_DTYPE = {LRSA_F32: torch.float32, LRSA_BF16: torch.bfloat16}
+
+
+def _expect(name: str, t: Optional[torch.Tensor], shape, stride, dtype, device) -> None:
+    """The C ABI describes Q, O, dO, dQ by ONE stride triple and K, V, dK, dV by another, and takes score, idx,
+    lse as contiguous: a tensor that differs would be read or written at wrong addresses, so it is refused."""
+    if t is None:
+        return
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(t.shape)}, expected {tuple(shape)}")
+    if t.dtype != dtype:
+        raise ValueError(f"{name}: dtype {t.dtype}, expected {dtype}")
+    if t.device != device:
+        raise ValueError(f"{name}: on {t.device}, expected {device}")
+    if stride is None:
+        if not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous")
+    else:
+        for dim, (have, want) in enumerate(zip(t.stride(), stride)):
+            if t.shape[dim] > 1 and have != want:
+                raise ValueError(f"{name}: stride {tuple(t.stride())}, the params describe {tuple(stride)}")
+
+
+def _expect_q(p: LrsaParams, device, **tensors) -> None:
+    shape = (p.batch, p.heads_q, p.seq, p.head_dim)
+    for name, t in tensors.items():
+        _expect(name, t, shape, (*p.q_stride, 1), _TORCH_DTYPE.get(p.dtype), device)
+
+
+def _expect_kv(p: LrsaParams, device, **tensors) -> None:
+    shape = (p.batch, p.heads_kv, p.seq, p.head_dim)
+    for name, t in tensors.items():
+        _expect(name, t, shape, (*p.kv_stride, 1), _TORCH_DTYPE.get(p.dtype), device)
+
+
 def _workspace(p: LrsaParams, which: int, device, ws: Optional[torch.Tensor]) -> Tuple[Optional[torch.Tensor], int]:
     need = workspace_bytes(p, which)
     if need == 0:
@@ -131,6 +165,8 @@ def lrsa_score(p: LrsaParams, K: torch.Tensor, V: torch.Tensor, score: Optional[
     Ns = num_scored_chunks(p)
     if score is None:
         score = torch.empty((p.batch, p.heads_kv, Ns, p.lag), dtype=torch.float32, device=K.device)
+    _expect_kv(p, K.device, K=K, V=V)
+    _expect("score", score, (p.batch, p.heads_kv, Ns, p.lag), None, torch.float32, K.device)
     ws, nb = _workspace(p, WS_SCORE, K.device, ws)
     _check(lib().lrsa_score(ctypes.byref(p), _ptr(K), _ptr(V), _ptr(score), _ptr(ws), nb, _stream()))
     return score
@@ -142,6 +178,8 @@ def lrsa_select(p: LrsaParams, score: torch.Tensor, idx: Optional[torch.Tensor] 
     Ns = num_scored_chunks(p)
     if idx is None:
         idx = torch.empty((p.batch, p.heads_kv, Ns, p.topk), dtype=torch.int32, device=score.device)
+    _expect("score", score, (p.batch, p.heads_kv, Ns, p.lag), None, torch.float32, score.device)
+    _expect("idx", idx, (p.batch, p.heads_kv, Ns, p.topk), None, torch.int32, score.device)
     ws, nb = _workspace(p, WS_SELECT, score.device, ws)
     _check(lib().lrsa_select(ctypes.byref(p), _ptr(score), _ptr(idx), _ptr(ws), nb, _stream()))
     return idx
@@ -155,6 +193,9 @@ def lrsa_score_select(p: LrsaParams, K: torch.Tensor, V: torch.Tensor, score: Op
         score = torch.empty((p.batch, p.heads_kv, Ns, p.lag), dtype=torch.float32, device=K.device)
     if idx is None:
         idx = torch.empty((p.batch, p.heads_kv, Ns, p.topk), dtype=torch.int32, device=K.device)
+    _expect_kv(p, K.device, K=K, V=V)
+    _expect("score", score, (p.batch, p.heads_kv, Ns, p.lag), None, torch.float32, K.device)
+    _expect("idx", idx, (p.batch, p.heads_kv, Ns, p.topk), None, torch.int32, K.device)
     ws, nb = _workspace(p, WS_SCORE, K.device, ws)
     _check(lib().lrsa_score_select(ctypes.byref(p), _ptr(K), _ptr(V), _ptr(score), _ptr(idx), _ptr(ws), nb, _stream()))
     return score, idx
@@ -191,6 +232,11 @@ def lrsa_attn_fwd(p: LrsaParams, Q, K, V, idx, O: Optional[torch.Tensor] = None,
         O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
     if lse is None:
         lse = torch.empty((p.batch, p.heads_q, p.seq), dtype=torch.float32, device=Q.device)
+    _expect_q(p, Q.device, Q=Q, O=O)
+    _expect_kv(p, Q.device, K=K, V=V)
+    _expect("lse", lse, (p.batch, p.heads_q, p.seq), None, torch.float32, Q.device)
+    if idx is not None:
+        _expect("idx", idx, (p.batch, p.heads_kv, num_scored_chunks(p), p.topk), None, torch.int32, Q.device)
     ws, nb = _workspace(p, WS_ATTN_FWD, Q.device, ws)
     _check(lib().lrsa_attn_fwd(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(O), _ptr(lse),
                                _ptr(ws), nb, _stream()))
@@ -203,6 +249,11 @@ def lrsa_attn_bwd(p: LrsaParams, Q, K, V, O, dO, lse, idx, dQ=None, dK=None, dV=
     dQ = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device) if dQ is None else dQ
     dK = torch.empty_strided(K.shape, K.stride(), dtype=K.dtype, device=K.device) if dK is None else dK
     dV = torch.empty_strided(K.shape, K.stride(), dtype=K.dtype, device=K.device) if dV is None else dV
+    _expect_q(p, Q.device, Q=Q, O=O, dO=dO, dQ=dQ)
+    _expect_kv(p, Q.device, K=K, V=V, dK=dK, dV=dV)
+    _expect("lse", lse, (p.batch, p.heads_q, p.seq), None, torch.float32, Q.device)
+    if idx is not None:
+        _expect("idx", idx, (p.batch, p.heads_kv, num_scored_chunks(p), p.topk), None, torch.int32, Q.device)
     ws, nb = _workspace(p, WS_ATTN_BWD, Q.device, ws)
     _check(lib().lrsa_attn_bwd(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(lse), _ptr(idx),
                                _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ws), nb, _stream()))

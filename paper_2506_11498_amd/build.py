@@ -10,14 +10,13 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-OBJ = os.environ.get("LRSA_OBJ_DIR", os.path.join(HERE, "_build"))
-LIB = os.environ.get("LRSA_LIB_OUT", os.path.join(HERE, "liblrsa.so"))
+OBJ = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "liblrsa.so")
 
-HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+HIPCC = "/opt/rocm/bin/hipcc"
 # packed-fp32 VALU forms are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
-FLAGS += os.environ.get("LRSA_EXTRA_HIPCC_FLAGS", "").split()   # e.g. -D switches for experiments
 
 
 # Kernels that count their own outstanding vector-memory operations (s_waitcnt vmcnt(n) around an
@@ -36,7 +35,7 @@ def _check_scratch(remarks: str, src: str) -> None:
         if m:
             name = m.group(1)
         m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
-        if not (m and name) or "generic" in name or "reduce" in name or os.environ.get("LRSA_ALLOW_SCRATCH"):
+        if not (m and name) or "generic" in name or "reduce" in name:
             continue
         for key, limit in SCRATCH_LIMIT.items():
             if key in name and int(m.group(1)) > limit:

@@ -474,12 +474,6 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
 #undef LRSA_OPND
 }
 
-#ifndef LRSA_DBG_NOCOMPUTE
-#define LRSA_DBG_NOCOMPUTE 0
-#endif
-#ifndef LRSA_DBG_NOLOAD
-#define LRSA_DBG_NOLOAD 0
-#endif
 // Two stages of 64 rows: one barrier per 64 MFMAs of a wave; the copies of the next stage run during
 // the two sub-steps of the current one.
 
@@ -617,7 +611,6 @@ __device__ __forceinline__ void dkv_body(const Dims& D, const bf16_t* __restrict
     // ---- loader: wave w fills rows 8w .. 8w+7 of the Q and dO tiles (two copies of 4 rows each) and
     // its own lse|D block (one copy each).
     auto issue = [&](int step, unsigned char* sQ, unsigned char* sG, float* sL) {
-        if (LRSA_DBG_NOLOAD) return;
         const int gi = step / sph;
         int r0, rend, lim_unused;
         step_rows(step, r0, rend, lim_unused);
@@ -664,7 +657,7 @@ __device__ __forceinline__ void dkv_body(const Dims& D, const bf16_t* __restrict
             /* every (row, key) pair of the sub-step visible for this wave? */                           \
             const bool full_ = wave_keys_valid && r0_ + KV_BQ <= rend_ &&                                \
                                (GATHER ? lim_u_ >= wave_key0 + 32 * KV_NB - 1 : r0_ >= wave_key0 + 32 * KV_NB - 1); \
-            if (run_ && !LRSA_DBG_NOCOMPUTE)                                                             \
+            if (run_)                                                                                    \
                 dkv_step<GATHER>(D, sQ, sG, sL + wave * 2 * KV_ROWS, kf, sVw, lo, dk, dv, r0_, rend_, kcmp, lim_u_, \
                                  !full_, c2, lane, sub_ * KV_BQ);                                        \
         }                                                                                                \

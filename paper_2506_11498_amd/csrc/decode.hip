@@ -6,8 +6,8 @@
 // k_cache_compress  one step for every (batch, KV head): the first L rows of the tail are scored against the
 //                   next L (Eq. 4-8, the same block routine as the training-time scoring), their top K are
 //                   kept in position order (text after Eq. 8) and the rest of the tail moves down by L - K
-//                   rows, in place ("the first chunk compressed and the second chunk retained as a sliding
-//                   window", Attention Filling 1).  An optional array of original positions moves alike.
+//                   rows, in place (Section 3.2, Attention Filling 1: the older chunk shrinks to its survivors,
+//                   the newer one stays whole).  An optional array of original positions moves alike.
 // k_decode_attn     single-query attention (Eq. 3, nothing masked) of the G query heads of a KV group over a
 //                   slice of the cache rows: fp32 online softmax, partial (max, sum, output) per slice;
 // k_decode_combine  merges the slices.

@@ -140,3 +140,25 @@ def test_inference_cache_calls_validate_on_the_host():
     # the condensed-cache variant asks for a larger attention workspace
     pc = _params(impl=binding.IMPL_COMPACT)
     assert lrsa.workspace_bytes(pc, binding.WS_ATTN_FWD) > lrsa.workspace_bytes(_params(), binding.WS_ATTN_FWD)
+
+
+def test_binding_refuses_tensors_whose_layout_differs_from_the_params():
+    """The ABI carries one stride triple for Q, O, dO, dQ and one for K, V, dK, dV; the binding refuses a
+    tensor laid out differently (before any GPU work) instead of letting the kernels address it wrongly."""
+    B, Hq, Hkv, n, d = 1, 4, 2, 16 + 5 * 32, 128
+    Q = torch.zeros(B, Hq, n, d, dtype=torch.bfloat16)
+    K = torch.zeros(B, Hkv, n, d, dtype=torch.bfloat16)
+    p = lrsa.params_for(Q, K, sink=16, lag=32, topk=8)
+    lse = torch.zeros(B, Hq, n)
+    idx = torch.zeros(B, Hkv, lrsa.num_scored_chunks(p), 8, dtype=torch.int32)
+    permuted = Q.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)          # same shape, other strides
+    with pytest.raises(ValueError, match="stride"):
+        lrsa.lrsa_attn_bwd(p, Q, K, K, Q, permuted, lse, idx)
+    with pytest.raises(ValueError, match="dtype"):
+        lrsa.lrsa_attn_fwd(p, Q, K, K.float(), idx)
+    with pytest.raises(ValueError, match="shape"):
+        lrsa.lrsa_attn_fwd(p, Q, K, K, idx[:, :, :-1])
+    with pytest.raises(ValueError, match="contiguous"):
+        lrsa.lrsa_attn_fwd(p, Q, K, K, idx, lse=torch.zeros(B, Hq, 2 * n)[:, :, ::2])
+    with pytest.raises(ValueError, match="dtype"):
+        lrsa.lrsa_select(p, torch.zeros(B, Hkv, idx.shape[2], 32, dtype=torch.float64))

@@ -9,6 +9,8 @@ Bars (written out here as the tests' tolerances):
   * O, dQ, dK, dV: max|x-ref|/max|ref| and ||x-ref||/||ref|| below 1e-4 (fp32) or 2e-2 (bf16)
     against the fp64 oracle fed the same stored inputs and the oracle's idx; lse within 1e-3.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -20,6 +22,7 @@ from oracle import lrsa_rows as rows
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def tol(dtype):
@@ -28,10 +31,12 @@ def tol(dtype):
 
 def rel_errs(x, r):
     x = np.asarray(x, np.float64); r = np.asarray(r, np.float64)
-    # the reference's own scale, floored so that an all-zero reference (a one-key softmax has zero
-    # dQ, dK) is compared absolutely against the O(1) scale of the inputs
-    top = max(np.abs(r).max(), 1e-2)
-    return np.abs(x - r).max() / top, np.linalg.norm(x - r) / max(np.linalg.norm(r), 1e-2 * np.sqrt(r.size))
+    top, nrm = np.abs(r).max(), np.linalg.norm(r)
+    if top == 0.0:
+        # an identically zero reference (a one-key softmax has dQ = dK = 0) has no scale of its own: the
+        # result is then compared absolutely, against the O(1) scale of the inputs
+        top, nrm = 1.0, np.sqrt(r.size)
+    return np.abs(x - r).max() / top, np.linalg.norm(x - r) / nrm
 
 
 def assert_close(name, x, r, t):
@@ -48,9 +53,11 @@ def params(w, x, **kw):
 
 
 def check_selection_in_tie_window(w, got, idx_ref, sc_ref):
-    """Returns the fraction of (b,h,p) windows that match exactly; asserts the tie-window bar."""
+    """Asserts the tie-window bar (every index on which the two sides differ has an oracle score within 1e-6
+    of the oracle's K-th largest score tau of its chunk).  Returns (fraction of (b,h,p) windows that match
+    exactly, number of differing indices whose oracle score lies outside the RELATIVE window 1e-5 * tau)."""
     got = got.reshape(-1, w.K); want = idx_ref.reshape(-1, w.K); sc = sc_ref.reshape(-1, w.L)
-    exact = 0
+    exact, outside_rel = 0, 0
     for a, b, s in zip(got, want, sc):
         base = b[0] - (b[0] - w.S) % w.L
         assert np.all(np.diff(a) > 0) and a[0] >= base and a[-1] < base + w.L, "idx contract broken"
@@ -59,8 +66,10 @@ def check_selection_in_tie_window(w, got, idx_ref, sc_ref):
             continue
         tau = np.sort(s)[-w.K]
         diff = np.setxor1d(a, b)
-        assert np.all(np.abs(s[diff - base] - tau) <= 1e-6), "selection differs outside the tie window"
-    return exact / max(len(got), 1)
+        gap = np.abs(s[diff - base] - tau)
+        assert np.all(gap <= 1e-6), "selection differs outside the tie window"
+        outside_rel += int(np.count_nonzero(gap > 1e-5 * tau))
+    return exact / max(len(got), 1), outside_rel
 
 
 def run_score_select(w, xd, **kw):
@@ -94,12 +103,14 @@ SMALL = [
 ]
 
 
-@pytest.mark.parametrize("impl", [lrsa.IMPL_AUTO, lrsa.IMPL_GENERIC], ids=["auto", "generic"])
+@pytest.mark.parametrize("impl", [lrsa.IMPL_AUTO, lrsa.IMPL_GENERIC, lrsa.IMPL_COMPACT], ids=["auto", "generic", "compact"])
 @pytest.mark.parametrize("cfg", SMALL, ids=[c["name"] for c in SMALL])
 @pytest.mark.parametrize("local_prev", [1, 2])
 def test_small_shapes_against_dense_oracle(cfg, impl, local_prev):
     if local_prev == 2 and cfg["name"] not in ("tail", "bf16_d128_gqa", "bf16_odd_sizes"):
         pytest.skip("local_prev=2 is exercised on three shapes")
+    if impl == lrsa.IMPL_COMPACT and not (cfg["dtype"] == "bf16" and cfg["d"] == 128):
+        pytest.skip("the condensed cache exists for the MFMA kernels (bf16, head_dim 128); elsewhere the flag is ignored")
     cfg = {k: v for k, v in cfg.items() if k != "name"}
     w = inputs.small_workload(**cfg)
     x = inputs.make_inputs(w)
@@ -237,10 +248,12 @@ def test_runs_are_deterministic():
 
 
 # ------------------------------------------------------------------ the five workloads
-def full_workload_parity(name, kv_heads, batch=0, n_rows=None, n_cols=None, late_cols_only=False, seed=0):
+def full_workload_parity(name, kv_heads, batch=0, n_rows=None, n_cols=None, seed=0, impl=lrsa.IMPL_AUTO,
+                         workload=None, progress=print):
     """Score / select on every head; attention on the listed KV groups of one batch entry,
-    either in full or on sampled rows / columns."""
-    w = inputs.WORKLOADS[name]
+    either in full or on sampled rows / columns.  `progress` receives a line after every stretch of oracle
+    work (long silent runs are taken for hangs)."""
+    w = workload if workload is not None else inputs.WORKLOADS[name]
     x = inputs.make_inputs(w)
     xd = {k: v.to(DEV) for k, v in x.items()}
     Kf, Vf = x["K"].float().numpy(), x["V"].float().numpy()
@@ -248,7 +261,7 @@ def full_workload_parity(name, kv_heads, batch=0, n_rows=None, n_cols=None, late
     idx_ref = ref.select(sc_ref, w.S, w.L, w.K)
     # the calls as bench.py makes them: one launch for score + select, preallocated outputs, one workspace
     # of the largest size shared by all calls
-    p = params(w, xd)
+    p = params(w, xd, impl=impl)
     Ns = lrsa.num_scored_chunks(p)
     ws = torch.empty(max(max(lrsa.workspace_bytes(p, k) for k in range(4)), 256), dtype=torch.uint8, device=DEV)
     score = torch.empty((w.B, w.Hkv, Ns, w.L), dtype=torch.float32, device=DEV)
@@ -258,8 +271,10 @@ def full_workload_parity(name, kv_heads, batch=0, n_rows=None, n_cols=None, late
     assert torch.equal(score2, score) and torch.equal(lrsa.lrsa_select(p, score2, None, ws), idx)
     assert np.allclose(to_np(score), sc_ref, rtol=2e-5, atol=1e-9)
     assert np.array_equal(lrsa.lrsa_select(p, torch.from_numpy(sc_ref).to(DEV)).cpu().numpy(), idx_ref)
-    exact = check_selection_in_tie_window(w, idx.cpu().numpy(), idx_ref, sc_ref)
-    print(f"{name}: end-to-end selection exact on {100 * exact:.2f}% of windows")
+    exact, outside_rel = check_selection_in_tie_window(w, idx.cpu().numpy(), idx_ref, sc_ref)
+    progress(f"{name}: end-to-end selection exact on {100 * exact:.2f}% of windows; differing indices outside the "
+             f"relative window 1e-5*tau: {outside_rel}")
+    assert outside_rel == 0
     idx_dev = torch.from_numpy(idx_ref).to(DEV)
     O, dQ = torch.empty_like(xd["Q"]), torch.empty_like(xd["Q"])
     lse = torch.empty((w.B, w.Hq, w.n), dtype=torch.float32, device=DEV)
@@ -275,17 +290,32 @@ def full_workload_parity(name, kv_heads, batch=0, n_rows=None, n_cols=None, late
         Qg, dOg = x["Q"][batch, sl].float().numpy(), x["dO"][batch, sl].float().numpy()
         args = (Qg, Kf[batch, h], Vf[batch, h], dOg, idx_ref[batch, h])
         if n_rows is None:
-            r = rows.attn_group(*args, w.S, w.L, w.K)
             rsel = csel = np.arange(w.n)
         else:
-            # rows: every segment boundary plus random ones; columns: sink, survivors, dropped
+            # rows: every segment boundary plus random ones
             edges = [0, w.S - 1, w.S, w.S + w.L - 1, w.S + w.L, w.S + 2 * w.L, w.n - 1, w.n - 2]
             rsel = np.unique(np.clip(np.concatenate([edges, rng.integers(0, w.n, n_rows)]), 0, w.n - 1))
-            lo = w.n - 3 * w.L if late_cols_only else 0
-            csel = np.unique(np.concatenate([rng.integers(lo, w.n, n_cols), idx_ref[batch, h, -1, :4],
-                                             [] if late_cols_only else [0, w.S - 1, w.S, idx_ref[batch, h, 0, 0]]])).astype(np.int64)
-            r = rows.attn_rows(*args, rsel, w.S, w.L, w.K)
-            r.update(rows.attn_cols(*args, csel, w.S, w.L, w.K))
+            # columns: random ones, sink tokens, survivors of the first, a middle and the last scored chunk (the
+            # longest sums: every later query of every head of the group adds to them), a dropped neighbour
+            mid = idx_ref.shape[2] // 2
+            csel = np.unique(np.concatenate([rng.integers(0, w.n, n_cols), [0, w.S - 1, w.S, w.n - 1],
+                                             idx_ref[batch, h, 0, :3], idx_ref[batch, h, mid, -3:],
+                                             idx_ref[batch, h, -1, :3], idx_ref[batch, h, 0, :1] + 1])).astype(np.int64)
+        # lse and D of every row that sees one of the columns (for sink and early-survivor columns: every later
+        # row), piece by piece; O and dQ are kept for the sampled rows
+        need = np.union1d(rsel, rows.rows_seeing(csel, w.n, w.S, w.L, idx_ref[batch, h]))
+        lse_all, D_all = np.full((G, w.n), np.nan), np.full((G, w.n), np.nan)
+        r = {"O": np.empty((G, len(rsel), w.d)), "dQ": np.empty((G, len(rsel), w.d)), "lse": np.empty((G, len(rsel)))}
+        for i0 in range(0, len(need), 8192):
+            piece = need[i0:i0 + 8192]
+            rp = rows.attn_rows(*args, piece, w.S, w.L, w.K)
+            lse_all[:, piece], D_all[:, piece] = rp["lse"], rp["D"]
+            keep = np.isin(piece, rsel)
+            at = np.searchsorted(rsel, piece[keep])
+            r["O"][:, at], r["dQ"][:, at], r["lse"][:, at] = rp["O"][:, keep], rp["dQ"][:, keep], rp["lse"][:, keep]
+            progress(f"{name} KV head {h}: oracle rows {i0 + len(piece)}/{len(need)}")
+        r.update(rows.attn_cols(*args, csel, w.S, w.L, w.K, lse_all=lse_all, D_all=D_all))
+        progress(f"{name} KV head {h}: oracle columns {len(csel)}")
         assert_close(f"O[h{h}]", to_np(O[batch, sl][:, rsel]), r["O"], t)
         assert np.abs(to_np(lse[batch, sl][:, rsel]) - r["lse"]).max() < 1e-3
         assert_close(f"dQ[h{h}]", to_np(dQ[batch, sl][:, rsel]), r["dQ"], t)
@@ -293,28 +323,61 @@ def full_workload_parity(name, kv_heads, batch=0, n_rows=None, n_cols=None, late
         assert_close(f"dV[h{h}]", to_np(dV[batch, h][csel]), r["dV"], t)
 
 
-def test_workload_C1_tiny_fp32():
-    full_workload_parity("C1", kv_heads=[0])
+@pytest.fixture
+def progress(capsys):
+    """Prints a line past pytest's capture and appends it to gpurun_out/progress.txt when that folder exists."""
+    def emit(msg):
+        with capsys.disabled():
+            print(msg, flush=True)
+        try:
+            with open(os.path.join(ROOT, "gpurun_out", "progress.txt"), "a") as f:
+                f.write(msg + "\n")
+        except OSError:
+            pass
+    return emit
 
 
-def test_workload_C2_small_bf16():
-    full_workload_parity("C2", kv_heads=[0, 5], batch=1)
+def test_workload_C1_tiny_fp32(progress):
+    full_workload_parity("C1", kv_heads=[0], progress=progress)
 
 
-def test_workload_C3_llama7b_shaped():
-    full_workload_parity("C3", kv_heads=[7, 20], n_rows=128, n_cols=32)
+def test_workload_C2_small_bf16(progress):
+    full_workload_parity("C2", kv_heads=[0, 5], batch=1, progress=progress)
 
 
-def test_workload_C4_gqa_32k():
-    full_workload_parity("C4", kv_heads=[0, 3, 7], n_rows=96, n_cols=16)
+@pytest.mark.parametrize("heads", [[0, 5, 7, 13], [20, 24, 29, 31]], ids=["h0-13", "h20-31"])
+def test_workload_C3_llama7b_shaped(heads, progress):
+    full_workload_parity("C3", kv_heads=heads, n_rows=256, n_cols=64, progress=progress)
 
 
-def test_workload_C6_paper_training_shape():
-    full_workload_parity("C6", kv_heads=[1], n_rows=160, n_cols=32)
+@pytest.mark.parametrize("heads", [[0, 1], [2, 3], [4, 5], [6, 7]], ids=["h0-1", "h2-3", "h4-5", "h6-7"])
+def test_workload_C4_gqa_32k(heads, progress):
+    """All 8 KV groups of the headline workload, two per test."""
+    full_workload_parity("C4", kv_heads=heads, n_rows=256, n_cols=64, seed=heads[0], progress=progress)
 
 
-def test_workload_C5_stress_128k():
-    full_workload_parity("C5", kv_heads=[1, 6], n_rows=64, n_cols=8, late_cols_only=True)
+def test_workload_C4_condensed_kv_cache(progress):
+    """The condensed-cache variant (impl = COMPACT) at full size, against the oracle."""
+    full_workload_parity("C4", kv_heads=[2], n_rows=192, n_cols=48, impl=lrsa.IMPL_COMPACT, seed=1, progress=progress)
+
+
+def test_workload_C6_paper_training_shape(progress):
+    full_workload_parity("C6", kv_heads=[0, 1], n_rows=256, n_cols=64, progress=progress)
+
+
+def test_c5_launch_plan_on_a_mid_size_shape_every_row_and_column(progress):
+    """64 query chunks and a group of 8 heads give the backward the plan it takes at C5 (4 query chunks per
+    slice, 16 slices, 8 heads per KV group); here the sequence is short enough for the oracle to check every
+    row of O, lse, dQ and every column of dK, dV of the group."""
+    w = inputs.small_workload("c5_plan", B=1, Hq=8, Hkv=1, d=128, n=64 + 63 * 128 + 100, L=128, K=32, S=64,
+                              dtype="bf16", seed=1105, structure="heavy_tokens")
+    full_workload_parity("c5_plan", kv_heads=[0], workload=w, progress=progress)
+
+
+def test_workload_C5_stress_128k(progress):
+    """One KV group (8 query heads): lse and D of every row (the sink and early-survivor columns are seen by
+    all of them) -- about two minutes of oracle time -- then sampled rows and columns."""
+    full_workload_parity("C5", kv_heads=[1], n_rows=128, n_cols=24, progress=progress)
 
 
 def test_whole_path_replays_from_a_captured_graph():

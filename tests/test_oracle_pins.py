@@ -88,6 +88,39 @@ def test_score_closed_form_from_golden_file():
     assert np.allclose(sc[0, 0, 0], 2 * np.array(vals["score_ddof1"]), rtol=1e-9)
 
 
+def _read_golden(name):
+    vals = {}
+    for line in open(os.path.join(GOLDEN, name)):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = line.split("=")
+            vals[k.strip()] = np.array([float(t) for t in v.split()])
+    return vals
+
+
+def test_score_adds_the_v_term_hand_example_with_k_different_from_v():
+    """Eq. 8 with K != V evaluated by hand (tests/golden/score_kv_hand_example.txt): the V term has its own
+    normalisation, Std and softmax; dropping it, or using K twice, gives other numbers."""
+    vals = _read_golden("score_kv_hand_example.txt")
+    mn, mx = vals["ref_min"], vals["ref_max"]
+
+    def tensor(pat_a, pat_b):
+        pat = vals["k_pattern_a"]
+        ref_rows = np.stack([mn + pat * (mx - mn), mn + (1 - pat) * (mx - mn)])   # per-channel min = mn, max = mx
+        filler = np.stack([mx * 3 + 1, mn * 5 - 2])                               # chunk 2: never used by chunk 0
+        return np.concatenate([np.stack([mn + pat_a * (mx - mn), mn + pat_b * (mx - mn)]), ref_rows, filler])[None, None]
+
+    Kt = tensor(vals["k_pattern_a"], vals["k_pattern_b"])
+    Vt = tensor(vals["v_pattern_a"], vals["v_pattern_b"])
+    assert np.allclose(vals["score_K"] + vals["score_V"], vals["score"], rtol=1e-12)
+    for dtype, rtol in ((np.float64, 1e-12), (np.float32, 1e-6)):
+        sc = ref.score(Kt, Vt, 0, 2, ddof=1, dtype=dtype)
+        assert sc.shape == (1, 1, 1, 2)
+        assert np.allclose(sc[0, 0, 0], vals["score"], rtol=rtol)
+        assert np.allclose(ref.score_one(Vt[0, 0], 0, 2, 1, 1, dtype)[0], vals["score_V"], rtol=rtol)
+    assert not np.allclose(ref.score(Kt, Kt, 0, 2, ddof=1, dtype=np.float64)[0, 0, 0], vals["score"], rtol=1e-3)
+
+
 def test_score_uses_following_chunk_not_own_chunk():
     """Eq. 4-5: min/max come from chunk p+1.  Scaling only chunk p+1 changes chunk p's score;
     changing chunk p+2 or chunk p-1 does not."""
