@@ -173,6 +173,20 @@ int lrsa_cache_compress(const lrsa_params *p, void *Kc, void *Vc, int32_t *pos, 
 int lrsa_decode_attn(const lrsa_params *p, const void *q, const void *Kc, const void *Vc, int32_t len, void *O,
                      float *lse, void *ws, size_t ws_bytes, void *stream);
 
+/* lrsa_decode_attn for callers that cannot allocate device memory or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results (bit
+ * for bit) as lrsa_decode_attn, but the partial records of the key slices live in an array inside the library
+ * (LRSA_DECODE_STATIC_SCRATCH_BYTES per GPU, held until the process ends) instead of `ws`.  The call allocates
+ * and frees nothing (leave lrsa_timing_enable off: timing creates events); the first call on a device looks up
+ * the array's address on that device.  A call that needs more than the array holds --
+ * batch * heads_q * slices * (head_dim + 2) * 4 bytes, slices = min(256, ceil(len / 256),
+ * ceil(512 / (batch * heads_kv))) -- fails with LRSA_ERR_INVALID_ARG and launches nothing.
+ * All calls on one GPU share the one array: calls that overlap in time on the same GPU (different streams,
+ * different threads) race; order them on one stream.  Nothing needs clearing between calls. */
+#define LRSA_DECODE_STATIC_SCRATCH_BYTES (4u << 20)
+int lrsa_decode_attn_static(const lrsa_params *p, const void *q, const void *Kc, const void *Vc, int32_t len,
+                            void *O, float *lse, void *stream);
+
 /* Message of the calling thread's last failed call (static thread-local storage, never NULL). */
 const char *lrsa_last_error(void);
 

@@ -21,7 +21,7 @@ WS_SCORE, WS_SELECT, WS_ATTN_FWD, WS_ATTN_BWD, WS_DECODE_ATTN = 0, 1, 2, 3, 4
 
 EXPORTS = ("lrsa_abi_version", "lrsa_last_error", "lrsa_num_scored_chunks", "lrsa_workspace_bytes",
            "lrsa_score", "lrsa_select", "lrsa_score_select", "lrsa_attn_fwd", "lrsa_attn_bwd",
-           "lrsa_cache_compress", "lrsa_decode_attn",
+           "lrsa_cache_compress", "lrsa_decode_attn", "lrsa_decode_attn_static",
            "lrsa_timing_enable", "lrsa_timing_count", "lrsa_timing_read")
 
 
@@ -64,6 +64,7 @@ def lib() -> ctypes.CDLL:
         L.lrsa_score_select.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
         L.lrsa_cache_compress.argtypes = [vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp]
         L.lrsa_decode_attn.argtypes = [vp, vp, vp, vp, ctypes.c_int32, vp, vp, vp, sz, vp]
+        L.lrsa_decode_attn_static.argtypes = [vp, vp, vp, vp, ctypes.c_int32, vp, vp, vp]
         L.lrsa_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.lrsa_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         _lib = L
@@ -222,6 +223,14 @@ def lrsa_decode_attn(p: LrsaParams, q: torch.Tensor, Kc: torch.Tensor, Vc: torch
     ws, nb = _workspace(p, WS_DECODE_ATTN, q.device, ws)
     _check(lib().lrsa_decode_attn(ctypes.byref(p), _ptr(q), _ptr(Kc), _ptr(Vc), int(length), _ptr(O), _ptr(lse),
                                   _ptr(ws), nb, _stream()))
+    return O, lse
+
+
+def lrsa_decode_attn_static(p: LrsaParams, q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, length: int,
+                            O: torch.Tensor, lse: Optional[torch.Tensor]):
+    """lrsa_decode_attn without a workspace (the library's built-in scratch array); O and lse are the caller's."""
+    _check(lib().lrsa_decode_attn_static(ctypes.byref(p), _ptr(q), _ptr(Kc), _ptr(Vc), int(length), _ptr(O), _ptr(lse),
+                                         _stream()))
     return O, lse
 
 

@@ -187,6 +187,24 @@ int lrsa_decode_attn(const lrsa_params* p, const void* q, const void* Kc, const 
     return hip_result(lrsa::launch_decode_attn(D, q, Kc, Vc, len, O, lse, ws, (hipStream_t)stream), "lrsa_decode_attn");
 }
 
+int lrsa_decode_attn_static(const lrsa_params* p, const void* q, const void* Kc, const void* Vc, int32_t len, void* O,
+                            float* lse, void* stream) {
+    lrsa::Dims D;
+    int rc = make_dims(p, &D);
+    if (rc != LRSA_OK) return rc;
+    if (len < 1 || len > D.n) return fail(LRSA_ERR_INVALID_ARG, "lrsa_decode_attn_static: len %d outside [1, cap=%d]", len, D.n);
+    if (!q || !Kc || !Vc || !O) return fail(LRSA_ERR_INVALID_ARG, "lrsa_decode_attn_static: q, Kc, Vc and O must not be NULL");
+    if (misaligned16(q) || misaligned16(Kc) || misaligned16(Vc))
+        return fail(LRSA_ERR_INVALID_ARG, "lrsa_decode_attn_static: q, Kc and Vc must be 16-byte aligned");
+    const size_t need = lrsa::decode_static_need(D, len);
+    if (need > lrsa::DECODE_STATIC_SCRATCH_BYTES)
+        return fail(LRSA_ERR_INVALID_ARG,
+                    "lrsa_decode_attn_static: this call needs %zu bytes of scratch, the built-in array holds %zu "
+                    "(batch * heads_q * slices too large); use lrsa_decode_attn with a workspace",
+                    need, (size_t)lrsa::DECODE_STATIC_SCRATCH_BYTES);
+    return hip_result(lrsa::launch_decode_attn_static(D, q, Kc, Vc, len, O, lse, (hipStream_t)stream), "lrsa_decode_attn_static");
+}
+
 int lrsa_attn_fwd(const lrsa_params* p, const void* Q, const void* K, const void* V, const int32_t* idx, void* O,
                   float* lse, void* ws, size_t ws_bytes, void* stream) {
     lrsa::Dims D;

@@ -41,6 +41,11 @@ bool cache_compress_supported(const Dims&);
 hipError_t launch_cache_compress(const Dims&, void* Kc, void* Vc, int32_t* pos, int len, int done, int steps, hipStream_t st);
 hipError_t launch_decode_attn(const Dims&, const void* q, const void* Kc, const void* Vc, int len, void* O, float* lse,
                               void* ws, hipStream_t st);
+// lrsa_decode_attn_static: bytes of the library-owned scratch array and what a call needs of it
+constexpr size_t DECODE_STATIC_SCRATCH_BYTES = size_t(4) << 20;
+size_t decode_static_need(const Dims&, int len);
+hipError_t launch_decode_attn_static(const Dims&, const void* q, const void* Kc, const void* Vc, int len, void* O,
+                                     float* lse, hipStream_t st);
 hipError_t launch_score_select(const Dims&, const void* K, const void* V, float* score, int32_t* idx, void* ws, hipStream_t st);
 
 size_t attn_fwd_generic_ws_bytes(const Dims&);

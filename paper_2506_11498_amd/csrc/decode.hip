@@ -15,6 +15,8 @@
 #include "score_block.h"
 #include "select_block.h"
 
+#include <mutex>
+
 namespace lrsa {
 
 constexpr int DEC_THREADS = 256;
@@ -245,6 +247,53 @@ __global__ __launch_bounds__(128) void k_decode_combine(Dims D, const float* __r
     }
     Elem<T>::put(O + bhq * D.d + ch, o / l);
     if (lse && ch == 0) lse[bhq] = (m + __builtin_log2f(l)) * 0.6931471805599453f;
+}
+
+// ------------------------------------------------------------------------------------ no-allocation variant
+// Scratch of lrsa_decode_attn_static: the partial (max, sum, output) records of the slices live in this array
+// instead of a caller's workspace.  Every GPU holds its own copy at its own address; the array's name is only a
+// host-side handle, so the device address is looked up once per device and that pointer is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[DECODE_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+static hipError_t scratch_address(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));   // address of the current device's copy
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+size_t decode_static_need(const Dims& D, int len) {
+    return size_t(D.B) * D.Hq * decode_splits(D, len) * (D.d + 2) * 4;
+}
+
+hipError_t launch_decode_attn(const Dims& D, const void* q, const void* Kc, const void* Vc, int len, void* O,
+                              float* lse, void* ws, hipStream_t st);
+
+// Same kernels, same slices, hence the same bits as launch_decode_attn; the caller has checked
+// decode_static_need() <= DECODE_STATIC_SCRATCH_BYTES.  Nothing has to start at zero: every record that the
+// combine kernel reads is written by the slice kernel of the same call.
+hipError_t launch_decode_attn_static(const Dims& D, const void* q, const void* Kc, const void* Vc, int len, void* O,
+                                     float* lse, hipStream_t st) {
+    void* part = nullptr;
+    const hipError_t e = scratch_address(&part);
+    if (e != hipSuccess) return e;
+    return launch_decode_attn(D, q, Kc, Vc, len, O, lse, part, st);
 }
 
 hipError_t launch_decode_attn(const Dims& D, const void* q, const void* Kc, const void* Vc, int len, void* O,
