@@ -77,6 +77,53 @@ def cpu_baseline(w, x, chunks=24):
             "tokens_per_s_extrapolated": w.B * w.n / t_full}
 
 
+def inference_bench(w, dev, batches=(1, 8), iters=50):
+    """The inference-time cache at the history length of the workload (context only, not part of `value`):
+    lrsa_decode_attn over the cache the last token of an n-token history sees (sink + K rows per compressed chunk +
+    the uncompressed tail) and one lrsa_cache_compress step on a cache whose tail has just reached two chunks.
+    Times are per-call sums of the kernels' HIP-event durations; GB/s = cache bytes the call must read / time."""
+    import torch
+    import paper_2506_11498_amd as lrsa
+    nchunks = (w.n - w.S) // w.L                     # full chunks of the history
+    done = max(nchunks - 1, 0)                       # the last full chunk is still the local window
+    length = w.S + w.K * done + (w.n - w.S - done * w.L)
+    cap = length + 2 * w.L
+    out = {"history_tokens": w.n, "cache_rows": length, "compressed_chunks": done}
+    esz = 2 if w.dtype == "bf16" else 4
+    for B in batches:
+        g = torch.Generator(device=dev).manual_seed(5)
+        Kc = torch.randn((B, w.Hkv, cap, w.d), generator=g, device=dev).to(w.torch_dtype)
+        Vc = torch.randn((B, w.Hkv, cap, w.d), generator=g, device=dev).to(w.torch_dtype)
+        q = torch.randn((B, w.Hq, w.d), generator=g, device=dev).to(w.torch_dtype)
+        p = lrsa.make_params((B, w.Hq, cap, w.d), tuple(Kc.shape), (w.Hq * cap * w.d, cap * w.d, w.d, 1), Kc.stride(),
+                             dtype=w.torch_dtype, sink=w.S, lag=w.L, topk=w.K)
+        O = torch.empty_like(q)
+        lse = torch.empty((B, w.Hq), dtype=torch.float32, device=dev)
+        ws = torch.empty(max(lrsa.workspace_bytes(p, 4), 256), dtype=torch.uint8, device=dev)
+        full = w.S + w.K * done + 2 * w.L            # a tail of exactly two chunks: one compression step
+        for timed in (False, True):
+            if timed:
+                torch.cuda.synchronize()
+                lrsa.timing_enable(True)
+            for _ in range(iters if timed else 5):
+                lrsa.lrsa_decode_attn(p, q, Kc, Vc, length, O, lse, ws)
+                lrsa.lrsa_cache_compress(p, Kc, Vc, None, full, done)
+        torch.cuda.synchronize()
+        per = {}
+        for name, ms in lrsa.timing_records():
+            per[name] = per.get(name, 0.0) + ms
+        lrsa.timing_enable(False)
+        attn_us = (per.get("k_decode_attn", 0.0) + per.get("k_decode_combine", 0.0)) * 1e3 / iters
+        comp_us = per.get("k_cache_compress", 0.0) * 1e3 / iters
+        attn_bytes = 2 * B * w.Hkv * length * w.d * esz
+        comp_bytes = 2 * B * w.Hkv * (2 * w.L + (w.K + w.L)) * w.d * esz * 1   # two chunks read, survivors + tail moved
+        out[f"B{B}"] = {"decode_attn_us": attn_us, "decode_attn_GBps": attn_bytes / attn_us / 1e3,
+                        "decode_attn_frac_of_hbm_peak": attn_bytes / attn_us / 1e3 / HBM_PEAK_GBPS,
+                        "cache_bytes": attn_bytes, "cache_compress_us": comp_us,
+                        "cache_compress_GBps": comp_bytes / max(comp_us, 1e-9) / 1e3}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -89,6 +136,8 @@ def main():
                     help="compact: attention over a physically condensed KV cache (LRSA_IMPL_COMPACT)")
     ap.add_argument("--separate-score-select", action="store_true",
                     help="call lrsa_score and lrsa_select (two launches) instead of lrsa_score_select (one)")
+    ap.add_argument("--no-inference", action="store_true",
+                    help="skip the inference-time cache measurement (lrsa_decode_attn, lrsa_cache_compress)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, run one plain 1 GiB device copy (a kernel of known traffic "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -213,6 +262,8 @@ def main():
         torch.cuda.synchronize()
         dst.copy_(src)
         torch.cuda.synchronize()
+    if not args.no_inference and w.L <= 4096:
+        out["inference_cache"] = inference_bench(w, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x)
     print(json.dumps(out))

@@ -143,6 +143,34 @@ int lrsa_attn_bwd(const lrsa_params *p, const void *Q, const void *K, const void
                   const void *dO, const float *lse, const int32_t *idx,
                   void *dQ, void *dK, void *dV, void *ws, size_t ws_bytes, void *stream);
 
+/* ---- attention by filling steps (Section 3.2, "Attention Filling 1 / 2 / repeat": the sequence is attended a few
+ * chunks at a time against a cache of sink + survivors + the previous chunk, so that the activations that live at
+ * once are those of m chunks, not of the whole sequence).
+ *
+ * A step covers the query rows [row_begin, row_end): row_begin is 0 or a chunk start S + qL, row_end a chunk start
+ * or the end of the sequence; the sink rows belong to the step that starts at 0.  The mask is the one of
+ * lrsa_attn_fwd (it does not depend on how many chunks a step takes), so the steps together give exactly the
+ * results of the one-shot calls: O, lse and dQ bit for bit, dK and dV up to the order of fp32 additions.
+ *   Q, O, dO, dQ : [B, Hq, row_end - row_begin, d_h] by q_stride -- the rows of the step only
+ *   lse          : [B, Hq, row_end - row_begin] fp32, contiguous
+ *   K, V         : [B, Hkv, n, d_h] by kv_stride; rows at and after row_end are not read
+ *   idx          : [B, Hkv, Ns, K] as for lrsa_attn_fwd; only the rows of chunks that are compressed for the step's
+ *                  queries (chunks < row_end's chunk - local_prev) are read, later rows may still be unwritten
+ *   dK_acc, dV_acc : [B, Hkv, n, d_h] fp32, contiguous: lrsa_attn_bwd_fill ADDS the step's share (the caller zeroes
+ *                  them before the first step; steps in any order, one after the other on one stream);
+ *                  lrsa_attn_bwd_finish converts the sums to dK, dV (by kv_stride, dtype `dtype`)
+ * Workspace: lrsa_fill_workspace_bytes(p, row_begin, row_end, LRSA_WS_ATTN_FWD / LRSA_WS_ATTN_BWD) -- it grows
+ * with the rows of the step and the cache they see, not with n * n_q.  Built for bf16 with head_dim 128
+ * (LRSA_ERR_UNSUPPORTED otherwise); impl LRSA_IMPL_COMPACT is treated as LRSA_IMPL_AUTO. */
+size_t lrsa_fill_workspace_bytes(const lrsa_params *p, int32_t row_begin, int32_t row_end, int which);
+int lrsa_attn_fwd_fill(const lrsa_params *p, int32_t row_begin, int32_t row_end, const void *Q, const void *K,
+                       const void *V, const int32_t *idx, void *O, float *lse, void *ws, size_t ws_bytes, void *stream);
+int lrsa_attn_bwd_fill(const lrsa_params *p, int32_t row_begin, int32_t row_end, const void *Q, const void *K,
+                       const void *V, const void *O, const void *dO, const float *lse, const int32_t *idx, void *dQ,
+                       float *dK_acc, float *dV_acc, void *ws, size_t ws_bytes, void *stream);
+int lrsa_attn_bwd_finish(const lrsa_params *p, const float *dK_acc, const float *dV_acc, void *dK, void *dV,
+                         void *stream);
+
 /* ---- inference-time LagKV cache (the setting of the paper's evaluation: the cache compressed lag window by
  * lag window while tokens are generated; Section 3.2, Attention Filling 1: once a second chunk is complete the
  * chunk before it is cut down to its survivors and the newer one stays whole as the local window).

@@ -22,6 +22,7 @@ WS_SCORE, WS_SELECT, WS_ATTN_FWD, WS_ATTN_BWD, WS_DECODE_ATTN = 0, 1, 2, 3, 4
 EXPORTS = ("lrsa_abi_version", "lrsa_last_error", "lrsa_num_scored_chunks", "lrsa_workspace_bytes",
            "lrsa_score", "lrsa_select", "lrsa_score_select", "lrsa_attn_fwd", "lrsa_attn_bwd",
            "lrsa_cache_compress", "lrsa_decode_attn", "lrsa_decode_attn_static",
+           "lrsa_fill_workspace_bytes", "lrsa_attn_fwd_fill", "lrsa_attn_bwd_fill", "lrsa_attn_bwd_finish",
            "lrsa_timing_enable", "lrsa_timing_count", "lrsa_timing_read")
 
 
@@ -65,6 +66,12 @@ def lib() -> ctypes.CDLL:
         L.lrsa_cache_compress.argtypes = [vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp]
         L.lrsa_decode_attn.argtypes = [vp, vp, vp, vp, ctypes.c_int32, vp, vp, vp, sz, vp]
         L.lrsa_decode_attn_static.argtypes = [vp, vp, vp, vp, ctypes.c_int32, vp, vp, vp]
+        i32 = ctypes.c_int32
+        L.lrsa_fill_workspace_bytes.restype = ctypes.c_size_t
+        L.lrsa_fill_workspace_bytes.argtypes = [vp, i32, i32, ctypes.c_int]
+        L.lrsa_attn_fwd_fill.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.lrsa_attn_bwd_fill.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.lrsa_attn_bwd_finish.argtypes = [vp, vp, vp, vp, vp, vp]
         L.lrsa_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.lrsa_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         _lib = L
@@ -267,6 +274,61 @@ def lrsa_attn_bwd(p: LrsaParams, Q, K, V, O, dO, lse, idx, dQ=None, dK=None, dV=
     _check(lib().lrsa_attn_bwd(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(lse), _ptr(idx),
                                _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ws), nb, _stream()))
     return dQ, dK, dV
+
+
+def fill_workspace_bytes(p: LrsaParams, row_begin: int, row_end: int, which: int) -> int:
+    return int(lib().lrsa_fill_workspace_bytes(ctypes.byref(p), int(row_begin), int(row_end), which))
+
+
+def _fill_ws(p, row_begin, row_end, which, device, ws):
+    need = fill_workspace_bytes(p, row_begin, row_end, which)
+    if ws is None:
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return ws, ws.numel() * ws.element_size()
+
+
+def lrsa_attn_fwd_fill(p: LrsaParams, row_begin: int, row_end: int, Q, K, V, idx, O=None, lse=None, ws=None):
+    """One filling step of the forward: Q, O hold the rows [row_begin, row_end) only; returns (O, lse)."""
+    rows = row_end - row_begin
+    if O is None:
+        O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    if lse is None:
+        lse = torch.empty((p.batch, p.heads_q, rows), dtype=torch.float32, device=Q.device)
+    shape = (p.batch, p.heads_q, rows, p.head_dim)
+    for name, t in (("Q", Q), ("O", O)):
+        _expect(name, t, shape, (*p.q_stride, 1), _TORCH_DTYPE.get(p.dtype), Q.device)
+    _expect_kv(p, Q.device, K=K, V=V)
+    _expect("lse", lse, (p.batch, p.heads_q, rows), None, torch.float32, Q.device)
+    ws, nb = _fill_ws(p, row_begin, row_end, WS_ATTN_FWD, Q.device, ws)
+    _check(lib().lrsa_attn_fwd_fill(ctypes.byref(p), int(row_begin), int(row_end), _ptr(Q), _ptr(K), _ptr(V), _ptr(idx),
+                                    _ptr(O), _ptr(lse), _ptr(ws), nb, _stream()))
+    return O, lse
+
+
+def lrsa_attn_bwd_fill(p: LrsaParams, row_begin: int, row_end: int, Q, K, V, O, dO, lse, idx, dK_acc, dV_acc,
+                       dQ=None, ws=None):
+    """One filling step of the backward: dQ of the rows, and their share ADDED to the fp32 sums dK_acc, dV_acc."""
+    rows = row_end - row_begin
+    dQ = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device) if dQ is None else dQ
+    shape = (p.batch, p.heads_q, rows, p.head_dim)
+    for name, t in (("Q", Q), ("O", O), ("dO", dO), ("dQ", dQ)):
+        _expect(name, t, shape, (*p.q_stride, 1), _TORCH_DTYPE.get(p.dtype), Q.device)
+    _expect_kv(p, Q.device, K=K, V=V)
+    for name, t in (("dK_acc", dK_acc), ("dV_acc", dV_acc)):
+        _expect(name, t, (p.batch, p.heads_kv, p.seq, p.head_dim), None, torch.float32, Q.device)
+    _expect("lse", lse, (p.batch, p.heads_q, rows), None, torch.float32, Q.device)
+    ws, nb = _fill_ws(p, row_begin, row_end, WS_ATTN_BWD, Q.device, ws)
+    _check(lib().lrsa_attn_bwd_fill(ctypes.byref(p), int(row_begin), int(row_end), _ptr(Q), _ptr(K), _ptr(V), _ptr(O),
+                                    _ptr(dO), _ptr(lse), _ptr(idx), _ptr(dQ), _ptr(dK_acc), _ptr(dV_acc), _ptr(ws), nb,
+                                    _stream()))
+    return dQ
+
+
+def lrsa_attn_bwd_finish(p: LrsaParams, dK_acc, dV_acc, dK, dV):
+    """fp32 sums of the filling steps -> dK, dV."""
+    _expect_kv(p, dK_acc.device, dK=dK, dV=dV)
+    _check(lib().lrsa_attn_bwd_finish(ctypes.byref(p), _ptr(dK_acc), _ptr(dV_acc), _ptr(dK), _ptr(dV), _stream()))
+    return dK, dV
 
 
 def timing_enable(on: bool) -> None:

@@ -64,6 +64,9 @@ int make_dims(const lrsa_params* p, lrsa::Dims* D) {
     D->dtype = p->dtype;
     D->compact = p->impl == LRSA_IMPL_COMPACT ? 1 : 0;
     for (int i = 0; i < 3; ++i) { D->qs[i] = p->q_stride[i]; D->ks[i] = p->kv_stride[i]; }
+    D->row_begin = 0; D->row_end = D->n; D->fq0 = 0; D->fq1 = D->nq;      // every query row
+    D->lse_stride = D->n;
+    D->acc = 0;
     if (p->batch * (int64_t)p->heads_kv * 2 > 65535 || p->heads_q > 65535 || D->Ns > 65535)
         return fail(LRSA_ERR_UNSUPPORTED, "batch*heads or chunk count beyond the launch grid limits");
     return LRSA_OK;
@@ -234,9 +237,105 @@ int lrsa_attn_bwd(const lrsa_params* p, const void* Q, const void* K, const void
         return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_bwd: tensors must be 16-byte aligned");
     if ((rc = check_ws(p, D, LRSA_WS_ATTN_BWD, ws, ws_bytes)) != LRSA_OK) return rc;
     const hipError_t e =
-        use_mfma(p, D) ? lrsa::launch_attn_bwd_mfma(D, Q, K, V, O, dO, lse, idx, dQ, dK, dV, ws, (hipStream_t)stream)
+        use_mfma(p, D) ? lrsa::launch_attn_bwd_mfma(D, Q, K, V, O, dO, lse, idx, dQ, dK, dV, nullptr, nullptr, ws, (hipStream_t)stream)
                        : lrsa::launch_attn_bwd_generic(D, Q, K, V, O, dO, lse, idx, dQ, dK, dV, ws, (hipStream_t)stream);
     return hip_result(e, "lrsa_attn_bwd");
+}
+
+}  // extern "C"
+
+namespace {
+
+// Row window of one filling step: [row_begin, row_end) must start at 0 or at a chunk start and end at a chunk
+// start or at the end of the sequence.  Fills the window fields of the derived dimensions.
+int set_row_window(lrsa::Dims* D, int32_t row_begin, int32_t row_end, const char* who) {
+    const int n = D->n, S = D->S, L = D->L;
+    if (row_begin < 0 || row_end > n || row_begin >= row_end)
+        return fail(LRSA_ERR_INVALID_ARG, "%s: rows [%d, %d) are not a window of [0, %d)", who, row_begin, row_end, n);
+    const bool begin_ok = row_begin == 0 || (row_begin >= S && (row_begin - S) % L == 0);
+    const bool end_ok = row_end == n || (row_end >= S && (row_end - S) % L == 0);
+    if (!begin_ok || !end_ok)
+        return fail(LRSA_ERR_INVALID_ARG, "%s: rows [%d, %d) do not start and end on chunk boundaries (sink %d, lag %d)", who,
+                    row_begin, row_end, S, L);
+    D->row_begin = row_begin;
+    D->row_end = row_end;
+    D->fq0 = row_begin <= S ? 0 : (row_begin - S) / L;
+    D->fq1 = row_end == n ? D->nq : (row_end - S) / L;
+    D->lse_stride = row_end - row_begin;
+    D->compact = 0;     // the condensed copy would be rebuilt at every step: the window calls gather by index
+    return LRSA_OK;
+}
+
+// base pointer such that row t of the caller's window tensor is addressed as row t of the sequence
+const void* shift_rows(const void* p, const lrsa::Dims& D, int64_t row_stride_elems) {
+    const int64_t esz = D.dtype == LRSA_BF16 ? 2 : 4;
+    return reinterpret_cast<const char*>(p) - int64_t(D.row_begin) * row_stride_elems * esz;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lrsa_fill_workspace_bytes(const lrsa_params* p, int32_t row_begin, int32_t row_end, int which) {
+    lrsa::Dims D;
+    if (make_dims(p, &D) != LRSA_OK || !use_mfma(p, D)) return 0;
+    if (set_row_window(&D, row_begin, row_end, "lrsa_fill_workspace_bytes") != LRSA_OK) return 0;
+    if (which == LRSA_WS_ATTN_FWD) return lrsa::attn_fwd_mfma_ws_bytes(D);
+    if (which == LRSA_WS_ATTN_BWD) return lrsa::attn_bwd_mfma_ws_bytes(D);
+    return 0;
+}
+
+int lrsa_attn_fwd_fill(const lrsa_params* p, int32_t row_begin, int32_t row_end, const void* Q, const void* K,
+                       const void* V, const int32_t* idx, void* O, float* lse, void* ws, size_t ws_bytes, void* stream) {
+    lrsa::Dims D;
+    int rc = make_dims(p, &D);
+    if (rc != LRSA_OK) return rc;
+    if (!use_mfma(p, D)) return fail(LRSA_ERR_UNSUPPORTED, "lrsa_attn_fwd_fill is built for bf16 with head_dim 128");
+    if ((rc = set_row_window(&D, row_begin, row_end, "lrsa_attn_fwd_fill")) != LRSA_OK) return rc;
+    if (!Q || !K || !V || !O || !lse) return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_fwd_fill: Q, K, V, O and lse must not be NULL");
+    if (D.fq1 - 1 - D.lp > 0 && !idx) return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_fwd_fill: idx is NULL but the rows see compressed chunks");
+    if (misaligned16(Q) || misaligned16(K) || misaligned16(V) || misaligned16(O))
+        return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_fwd_fill: tensors must be 16-byte aligned");
+    const size_t need = lrsa::attn_fwd_mfma_ws_bytes(D);
+    if (need > 0 && (!ws || ws_bytes < need)) return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_fwd_fill: workspace of %zu bytes needed", need);
+    return hip_result(lrsa::launch_attn_fwd_mfma(D, shift_rows(Q, D, D.qs[2]), K, V, idx,
+                                                 const_cast<void*>(shift_rows(O, D, D.qs[2])), lse - D.row_begin, ws,
+                                                 (hipStream_t)stream),
+                      "lrsa_attn_fwd_fill");
+}
+
+int lrsa_attn_bwd_fill(const lrsa_params* p, int32_t row_begin, int32_t row_end, const void* Q, const void* K,
+                       const void* V, const void* O, const void* dO, const float* lse, const int32_t* idx, void* dQ,
+                       float* dK_acc, float* dV_acc, void* ws, size_t ws_bytes, void* stream) {
+    lrsa::Dims D;
+    int rc = make_dims(p, &D);
+    if (rc != LRSA_OK) return rc;
+    if (!use_mfma(p, D)) return fail(LRSA_ERR_UNSUPPORTED, "lrsa_attn_bwd_fill is built for bf16 with head_dim 128");
+    if ((rc = set_row_window(&D, row_begin, row_end, "lrsa_attn_bwd_fill")) != LRSA_OK) return rc;
+    if (!Q || !K || !V || !O || !dO || !lse || !dQ || !dK_acc || !dV_acc)
+        return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_bwd_fill: tensor pointers must not be NULL");
+    if (D.fq1 - 1 - D.lp > 0 && !idx) return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_bwd_fill: idx is NULL but the rows see compressed chunks");
+    if (misaligned16(Q) || misaligned16(K) || misaligned16(V) || misaligned16(O) || misaligned16(dO) || misaligned16(dQ) ||
+        misaligned16(dK_acc) || misaligned16(dV_acc))
+        return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_bwd_fill: tensors must be 16-byte aligned");
+    const size_t need = lrsa::attn_bwd_mfma_ws_bytes(D);
+    if (!ws || ws_bytes < need) return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_bwd_fill: workspace of %zu bytes needed", need);
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return fail(LRSA_ERR_INVALID_ARG, "workspace is not 256-byte aligned");
+    D.acc = 1;
+    return hip_result(lrsa::launch_attn_bwd_mfma(D, shift_rows(Q, D, D.qs[2]), K, V, shift_rows(O, D, D.qs[2]),
+                                                 shift_rows(dO, D, D.qs[2]), lse - D.row_begin, idx,
+                                                 const_cast<void*>(shift_rows(dQ, D, D.qs[2])), nullptr, nullptr, dK_acc,
+                                                 dV_acc, ws, (hipStream_t)stream),
+                      "lrsa_attn_bwd_fill");
+}
+
+int lrsa_attn_bwd_finish(const lrsa_params* p, const float* dK_acc, const float* dV_acc, void* dK, void* dV, void* stream) {
+    lrsa::Dims D;
+    int rc = make_dims(p, &D);
+    if (rc != LRSA_OK) return rc;
+    if (!use_mfma(p, D)) return fail(LRSA_ERR_UNSUPPORTED, "lrsa_attn_bwd_finish is built for bf16 with head_dim 128");
+    if (!dK_acc || !dV_acc || !dK || !dV) return fail(LRSA_ERR_INVALID_ARG, "lrsa_attn_bwd_finish: pointers must not be NULL");
+    return hip_result(lrsa::launch_bwd_acc_finish(D, dK_acc, dV_acc, dK, dV, (hipStream_t)stream), "lrsa_attn_bwd_finish");
 }
 
 }  // extern "C"

@@ -35,40 +35,49 @@ constexpr int KV_MAX_SLICES = 16;
 
 // ------------------------------------------------------------------------------------ host-side plan
 struct BwdPlan {
-    int sink_tiles_k, tpc_k;    // dK/dV window mode: key tiles of 128
-    int gl_total, gtiles;       // gather list length per KV head, its tiles of 128
+    int sink_tiles_k, tpc_k;    // dK/dV window mode: key tiles of KV_BK positions in the sink / per chunk
+    int kc_lo, ktiles;          // first key chunk and number of key tiles of the window part
+    int fq0, fq1;               // query chunks whose rows take part (all of them unless a row window is set)
+    int gl_total, gtiles;       // gather list length per KV head as the last query chunk sees it, its tiles
     int qch, nsl;               // query chunks per slice, slices per gather tile (<= KV_MAX_SLICES)
     int gather_wgs;             // workgroups of the GATHER part of the dK/dV launch (a multiple of 8)
-    size_t off_lse2, off_part, off_compact, bytes;   // workspace: D, lse in log2 units, the fp32 partials, condensed K/V
+    size_t off_lse2, off_part, off_compact, off_dkc, bytes;   // workspace: D, lse in log2 units, the fp32 partials,
+                                                              // condensed K/V, condensed dK/dV (fp32)
 };
 
 static BwdPlan make_plan(const Dims& D) {
     BwdPlan P;
     const int sink_rows = D.S < D.n ? D.S : D.n;
-    P.sink_tiles_k = (sink_rows + KV_BK - 1) / KV_BK;
+    P.fq0 = D.fq0;
+    P.fq1 = D.fq1;
+    const int nqf = D.fq1 - D.fq0;                 // query chunks in the window
+    P.sink_tiles_k = D.row_begin == 0 ? (sink_rows + KV_BK - 1) / KV_BK : 0;   // sink keys see only sink queries here
     P.tpc_k = (D.L + KV_BK - 1) / KV_BK;
-    P.gl_total = D.nq > 0 ? D.S + D.K * D.Ns : 0;
+    P.kc_lo = D.fq0 - D.lp > 0 ? D.fq0 - D.lp : 0;  // the local window reaches lp chunks back
+    P.ktiles = P.sink_tiles_k + (D.fq1 - P.kc_lo) * P.tpc_k;
+    P.gl_total = D.fq1 > 0 ? gather_count(D, D.fq1 - 1) : 0;
     P.gtiles = (P.gl_total + KV_BK - 1) / KV_BK;
     // aim at ~8192 query rows (x G heads) per workgroup, but never more than KV_MAX_SLICES slices
     int64_t qch = (256 * 32) / (int64_t(D.L) * D.G);
     if (qch < 1) qch = 1;
-    const int min_qch = (D.nq + KV_MAX_SLICES - 1) / KV_MAX_SLICES;
+    const int min_qch = (nqf + KV_MAX_SLICES - 1) / KV_MAX_SLICES;
     if (qch < min_qch) qch = min_qch;
     if (qch < 1) qch = 1;
     // small problems: shorter slices (down to ~1024 query rows x G heads) until the gather workgroups -- about
     // half of the (tile, slice) grid sees any query -- fill the chip twice
     while (qch > min_qch && qch > 1 && (qch / 2) * int64_t(D.L) * D.G >= 1024 &&
-           int64_t(D.B) * D.Hkv * P.gtiles * ((D.nq + qch - 1) / qch) / 2 < 512)
+           int64_t(D.B) * D.Hkv * P.gtiles * ((nqf + qch - 1) / qch) / 2 < 512)
         qch /= 2;
     P.qch = int(qch);
-    P.nsl = D.nq > 0 ? (D.nq + P.qch - 1) / P.qch : 0;
-    P.off_lse2 = align256(size_t(D.B) * D.Hq * D.n * 4);
+    P.nsl = nqf > 0 ? (nqf + P.qch - 1) / P.qch : 0;
+    P.off_lse2 = align256(size_t(D.B) * D.Hq * D.lse_stride * 4);
     P.off_part = 2 * P.off_lse2;
     P.gather_wgs = P.gtiles > 0 ? (D.B * D.Hkv * P.nsl + 7) / 8 * 8 * P.gtiles : 0;
     // slots 0 .. nsl-1: the GATHER workgroups' slices; slot nsl: what the WINDOW workgroups add to listed positions
     const size_t part = size_t(2) * (P.nsl + 1) * D.B * D.Hkv * P.gl_total * 128 * 4;
     P.off_compact = P.off_part + align256(part);
-    P.bytes = P.off_compact + compact_kv_bytes(D);
+    P.off_dkc = P.off_compact + compact_kv_bytes(D);
+    P.bytes = P.off_dkc + (D.compact ? 2 * align256(size_t(D.B) * D.Hkv * P.gl_total * 128 * 4) : 0);
     return P;
 }
 
@@ -258,7 +267,7 @@ __global__ __launch_bounds__(DQ_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t* 
     }
     // D = rowsum(dO * O) of this lane's row and its lse in log2 units: used here and, through the workspace,
     // by the key-outer kernel that runs after this one (every (head, query) row belongs to exactly one wave)
-    const int64_t rowid = (int64_t(b) * D.Hq + hq) * D.n + tq_ld;
+    const int64_t rowid = (int64_t(b) * D.Hq + hq) * D.lse_stride + tq_ld;
     const float lse2 = lse[rowid] * 1.4426950408889634f;
     float Dq = 0.0f;
 #pragma unroll
@@ -495,11 +504,12 @@ __device__ __forceinline__ KvLds kv_lds() {
 
 template <bool GATHER>
 __device__ __forceinline__ void dkv_body(const Dims& D, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
-                                         const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO,
+                                         const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kc,
+                                         const bf16_t* __restrict__ Vc, const bf16_t* __restrict__ dO,
                                          const float* __restrict__ lse, const float* __restrict__ Dsum,
                                          const int32_t* __restrict__ idx, bf16_t* __restrict__ dK,
-                                         bf16_t* __restrict__ dV, float* __restrict__ part, const BwdPlan& P,
-                                         const int block) {
+                                         bf16_t* __restrict__ dV, float* __restrict__ accK, float* __restrict__ accV,
+                                         float* __restrict__ part, const BwdPlan& P, const int block) {
     const KvLds sh = kv_lds();
     unsigned char *const sQ0 = sh.sQ0, *const sQ1 = sh.sQ1, *const sG0 = sh.sG0, *const sG1 = sh.sG1;
     float *const sL0 = sh.sL0, *const sL1 = sh.sL1;
@@ -527,9 +537,8 @@ __device__ __forceinline__ void dkv_body(const Dims& D, const bf16_t* __restrict
             slice = P.nsl - 1 - grp / units;          // latest slices (most list tiles) first
             key0 = (seq % P.gtiles) * KV_BK;
         } else {
-            const int ktiles = P.sink_tiles_k + D.nq * P.tpc_k;
-            unit = block / ktiles;
-            key0 = ktiles - 1 - block % ktiles;   // tile index for now
+            unit = block / P.ktiles;
+            key0 = P.ktiles - 1 - block % P.ktiles;   // tile index for now
         }
     }
     const int h = unit % D.Hkv, b = unit / D.Hkv;
@@ -538,8 +547,8 @@ __device__ __forceinline__ void dkv_body(const Dims& D, const bf16_t* __restrict
         // slice = query chunks [slice*qch, (slice+1)*qch), of which the tile sees those from qf on
         key_end = P.gl_total;
         const int qf = first_chunk_seeing(D, key0);
-        qa = max(slice * P.qch, qf);
-        const int qb = min(D.nq, (slice + 1) * P.qch);
+        qa = max(P.fq0 + slice * P.qch, qf);
+        const int qb = min(P.fq1, P.fq0 + (slice + 1) * P.qch);
         if (qa >= qb) return;
         ta = D.S + qa * D.L;
         const int64_t e = int64_t(D.S) + int64_t(qb) * D.L;
@@ -549,18 +558,19 @@ __device__ __forceinline__ void dkv_body(const Dims& D, const bf16_t* __restrict
         if (tix < P.sink_tiles_k) {
             key0 = tix * KV_BK;
             key_end = D.S < D.n ? D.S : D.n;
-            tb = key_end;                         // only sink queries see sink keys through the window
+            tb = key_end < D.row_end ? key_end : D.row_end;   // only sink queries see sink keys through the window
         } else {
             const int tt = tix - P.sink_tiles_k;
-            const int kc = tt / P.tpc_k;
+            const int kc = P.kc_lo + tt / P.tpc_k;
             key0 = D.S + kc * D.L + (tt % P.tpc_k) * KV_BK;
             const int64_t e = int64_t(D.S) + int64_t(kc + 1) * D.L;
             key_end = e < D.n ? int(e) : D.n;
             const int64_t e2 = int64_t(D.S) + (int64_t(kc) + 1 + D.lp) * D.L;
-            tb = e2 < D.n ? int(e2) : D.n;
+            tb = e2 < D.row_end ? int(e2) : D.row_end;
         }
         if (key0 >= key_end) return;
-        ta = key0;
+        ta = key0 > D.row_begin ? key0 : D.row_begin;
+        if (ta >= tb) return;
     }
     // Steps of KV_ROWS rows.  WINDOW: consecutive rows of [ta, tb).  GATHER: chunk by chunk (the last step
     // of a chunk may be partial), so that one step never sees two different gather-list prefixes.
@@ -594,16 +604,26 @@ __device__ __forceinline__ void dkv_body(const Dims& D, const bf16_t* __restrict
         const int kidn = wave_key0 + nb * 32 + l32;
         const bool kvalid = kidn < key_end;
         const int kid_ld = kvalid ? kidn : key_end - 1;
-        const int kpos = GATHER ? (kid_ld < D.S ? kid_ld : idx_h[kid_ld - D.S]) : kid_ld;
         kcmp[nb] = kvalid ? kidn : 0x7fffffff;
-        const int64_t koff = b * D.ks[0] + h * D.ks[1] + int64_t(kpos) * D.ks[2];
+        // the key's K and V rows: by position, or (GATHER with a condensed cache) row kid of the contiguous copy
+        const bf16_t *krow, *vrow_src;
+        if (GATHER && D.compact) {
+            const int64_t coff = ((int64_t(b) * D.Hkv + h) * P.gl_total + kid_ld) * 128;
+            krow = Kc + coff;
+            vrow_src = Vc + coff;
+        } else {
+            const int kpos = GATHER ? (kid_ld < D.S ? kid_ld : idx_h[kid_ld - D.S]) : kid_ld;
+            const int64_t koff = b * D.ks[0] + h * D.ks[1] + int64_t(kpos) * D.ks[2];
+            krow = K + koff;
+            vrow_src = V + koff;
+        }
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) kf[nb][kk] = *reinterpret_cast<const bf16x8*>(K + koff + kk * 16 + g * 8);
+        for (int kk = 0; kk < 8; ++kk) kf[nb][kk] = *reinterpret_cast<const bf16x8*>(krow + kk * 16 + g * 8);
         const int vrow = wave * (32 * KV_NB) + nb * 32 + l32;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk)
             *reinterpret_cast<bf16x8*>(sVk + tile_off(vrow, kk * 2 + g)) =
-                *reinterpret_cast<const bf16x8*>(V + koff + kk * 16 + g * 8);
+                *reinterpret_cast<const bf16x8*>(vrow_src + kk * 16 + g * 8);
     }
     const unsigned char* sVw = sVk + wave * (32 * KV_NB) * TILE_ROW_BYTES;
     const LaneOffs lo = make_lane_offs(lane);
@@ -625,7 +645,7 @@ __device__ __forceinline__ void dkv_body(const Dims& D, const bf16_t* __restrict
             async_rows4(Q + off, sQ, r4);
             async_rows4(dO + off, sG, r4);
         }
-        const int64_t rid = (int64_t(b) * D.Hq + hq) * D.n + min(r0 + lane, rend - 1);
+        const int64_t rid = (int64_t(b) * D.Hq + hq) * D.lse_stride + min(r0 + lane, rend - 1);
         async_copy4(lse + rid, sL + wave * 2 * KV_ROWS);
         async_copy4(Dsum + rid, sL + wave * 2 * KV_ROWS + KV_ROWS);
     };
@@ -704,7 +724,7 @@ __device__ __forceinline__ void dkv_body(const Dims& D, const bf16_t* __restrict
                 if (kidn < D.S) j = kidn;
                 else {
                     const int c = (kidn - D.S) / D.L;
-                    if (c < D.Ns) {
+                    if (D.S + (c + 1) * D.K <= P.gl_total) {   // chunk c is compressed for some query of this call
                         const int32_t* rowp = idx_h + int64_t(c) * D.K;
                         int lo_ = 0, hi_ = D.K - 1;
                         while (lo_ <= hi_) {
@@ -730,6 +750,11 @@ __device__ __forceinline__ void dkv_body(const Dims& D, const bf16_t* __restrict
                     if (j >= 0) {
                         *reinterpret_cast<f32x4*>(pk + dcol) = x;
                         *reinterpret_cast<f32x4*>(pk + part_v + dcol) = y;
+                    } else if (D.acc) {
+                        // row window: this call's share is added to the caller's fp32 sums (one writer per element)
+                        const int64_t aoff = ((int64_t(b) * D.Hkv + h) * D.n + kidn) * 128 + dcol;
+                        *reinterpret_cast<f32x4*>(accK + aoff) += x;
+                        *reinterpret_cast<f32x4*>(accV + aoff) += y;
                     } else {
                         *reinterpret_cast<bf16x4*>(dK + koff + dcol) = __builtin_convertvector(x, bf16x4);
                         *reinterpret_cast<bf16x4*>(dV + koff + dcol) = __builtin_convertvector(y, bf16x4);
@@ -744,23 +769,29 @@ __device__ __forceinline__ void dkv_body(const Dims& D, const bf16_t* __restrict
 __global__ __launch_bounds__(KV_THREADS, KV_WAVES == 8 ? 2 : 1) void k_bwd_dkv(Dims D, const bf16_t* __restrict__ Q,
                                                                                 const bf16_t* __restrict__ K,
                                                                                 const bf16_t* __restrict__ V,
+                                                                                const bf16_t* __restrict__ Kc,
+                                                                                const bf16_t* __restrict__ Vc,
                                                                                 const bf16_t* __restrict__ dO,
                                                                                 const float* __restrict__ lse,
                                                                                 const float* __restrict__ Dsum,
                                                                                 const int32_t* __restrict__ idx,
                                                                                 bf16_t* __restrict__ dK,
                                                                                 bf16_t* __restrict__ dV,
+                                                                                float* __restrict__ accK,
+                                                                                float* __restrict__ accV,
                                                                                 float* __restrict__ part, BwdPlan P) {
     const int block = blockIdx.x;
-    if (block < P.gather_wgs) dkv_body<true>(D, Q, K, V, dO, lse, Dsum, idx, dK, dV, part, P, block);
-    else dkv_body<false>(D, Q, K, V, dO, lse, Dsum, idx, dK, dV, part, P, block - P.gather_wgs);
+    if (block < P.gather_wgs) dkv_body<true>(D, Q, K, V, Kc, Vc, dO, lse, Dsum, idx, dK, dV, accK, accV, part, P, block);
+    else dkv_body<false>(D, Q, K, V, Kc, Vc, dO, lse, Dsum, idx, dK, dV, accK, accV, part, P, block - P.gather_wgs);
 }
 
 // dK, dV of the listed positions (sink tokens and survivors): the WINDOW contribution plus the GATHER slices
 // that exist for the entry's list tile, added in a fixed order.  32 threads per entry, 4 channels each.
 __global__ __launch_bounds__(256) void k_bwd_dkv_reduce(Dims D, const int32_t* __restrict__ idx,
                                                         const float* __restrict__ part, bf16_t* __restrict__ dK,
-                                                        bf16_t* __restrict__ dV, BwdPlan P) {
+                                                        bf16_t* __restrict__ dV, float* __restrict__ accK,
+                                                        float* __restrict__ accV, float* __restrict__ dKc,
+                                                        float* __restrict__ dVc, BwdPlan P) {
     const int64_t e = int64_t(blockIdx.x) * 8 + (threadIdx.x >> 5);   // (b, h, entry)
     const int64_t total = int64_t(D.B) * D.Hkv * P.gl_total;
     if (e >= total) return;
@@ -772,36 +803,94 @@ __global__ __launch_bounds__(256) void k_bwd_dkv_reduce(Dims D, const int32_t* _
     const size_t part_v = size_t(P.nsl + 1) * part_stride;
     const int dcol = (threadIdx.x & 31) * 4;
     const float* p0 = part + size_t(e) * 128 + dcol;
-    f32x4 x = *reinterpret_cast<const f32x4*>(p0 + size_t(P.nsl) * part_stride);
-    f32x4 y = *reinterpret_cast<const f32x4*>(p0 + size_t(P.nsl) * part_stride + part_v);
+    f32x4 x = {0.0f, 0.0f, 0.0f, 0.0f}, y = {0.0f, 0.0f, 0.0f, 0.0f};
+    // the WINDOW workgroups of this call cover the sink (with a row window: only when its rows are in it) and the
+    // key chunks from kc_lo on
+    const bool in_window = pos < D.S ? P.sink_tiles_k > 0 : (pos - D.S) / D.L >= P.kc_lo;
+    if (in_window) {
+        x = *reinterpret_cast<const f32x4*>(p0 + size_t(P.nsl) * part_stride);
+        y = *reinterpret_cast<const f32x4*>(p0 + size_t(P.nsl) * part_stride + part_v);
+    }
     const int qf0 = first_chunk_seeing(D, (j / KV_BK) * KV_BK);
-    if (qf0 < D.nq)
-        for (int sl = qf0 / P.qch; sl < P.nsl; ++sl) {
+    if (qf0 < P.fq1)
+        for (int sl = qf0 > P.fq0 ? (qf0 - P.fq0) / P.qch : 0; sl < P.nsl; ++sl) {
             x += *reinterpret_cast<const f32x4*>(p0 + size_t(sl) * part_stride);
             y += *reinterpret_cast<const f32x4*>(p0 + size_t(sl) * part_stride + part_v);
         }
+    if (D.acc) {
+        const int64_t aoff = ((int64_t(b) * D.Hkv + h) * D.n + pos) * 128 + dcol;
+        *reinterpret_cast<f32x4*>(accK + aoff) += x;
+        *reinterpret_cast<f32x4*>(accV + aoff) += y;
+        return;
+    }
+    if (dKc) {   // condensed cache: the gradient of the condensed rows is a product of its own, scattered afterwards
+        *reinterpret_cast<f32x4*>(dKc + e * 128 + dcol) = x;
+        *reinterpret_cast<f32x4*>(dVc + e * 128 + dcol) = y;
+        return;
+    }
     const int64_t koff = b * D.ks[0] + h * D.ks[1] + int64_t(pos) * D.ks[2];
     *reinterpret_cast<bf16x4*>(dK + koff + dcol) = __builtin_convertvector(x, bf16x4);
     *reinterpret_cast<bf16x4*>(dV + koff + dcol) = __builtin_convertvector(y, bf16x4);
 }
 
+// Condensed cache: dKc, dVc [B, Hkv, gl, 128] fp32 -> rows of dK, dV at the positions of the gather list.  Every
+// position occurs once in the list, so the scatter has no collisions and needs no addition.
+__global__ __launch_bounds__(256) void k_bwd_scatter_dkv(Dims D, const int32_t* __restrict__ idx,
+                                                         const float* __restrict__ dKc, const float* __restrict__ dVc,
+                                                         bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, int gl) {
+    const int64_t e = int64_t(blockIdx.x) * 8 + (threadIdx.x >> 5);   // (b, h, entry)
+    if (e >= int64_t(D.B) * D.Hkv * gl) return;
+    const int j = int(e % gl), bh = int(e / gl);
+    const int b = bh / D.Hkv, h = bh % D.Hkv;
+    const int pos = j < D.S ? j : idx[(int64_t(bh) * D.Ns) * D.K + (j - D.S)];
+    const int dcol = (threadIdx.x & 31) * 4;
+    const int64_t koff = b * D.ks[0] + h * D.ks[1] + int64_t(pos) * D.ks[2];
+    *reinterpret_cast<bf16x4*>(dK + koff + dcol) = __builtin_convertvector(*reinterpret_cast<const f32x4*>(dKc + e * 128 + dcol), bf16x4);
+    *reinterpret_cast<bf16x4*>(dV + koff + dcol) = __builtin_convertvector(*reinterpret_cast<const f32x4*>(dVc + e * 128 + dcol), bf16x4);
+}
+
+// fp32 sums of a sequence of row-window calls -> dK, dV in the tensors' dtype (32 lanes per row)
+__global__ __launch_bounds__(256) void k_bwd_acc_finish(Dims D, const float* __restrict__ accK,
+                                                        const float* __restrict__ accV, bf16_t* __restrict__ dK,
+                                                        bf16_t* __restrict__ dV) {
+    const int64_t e = int64_t(blockIdx.x) * 8 + (threadIdx.x >> 5);   // (b, h, position)
+    if (e >= int64_t(D.B) * D.Hkv * D.n) return;
+    const int pos = int(e % D.n), bh = int(e / D.n);
+    const int b = bh / D.Hkv, h = bh % D.Hkv;
+    const int dcol = (threadIdx.x & 31) * 4;
+    const f32x4 x = *reinterpret_cast<const f32x4*>(accK + e * 128 + dcol);
+    const f32x4 y = *reinterpret_cast<const f32x4*>(accV + e * 128 + dcol);
+    const int64_t koff = b * D.ks[0] + h * D.ks[1] + int64_t(pos) * D.ks[2];
+    *reinterpret_cast<bf16x4*>(dK + koff + dcol) = __builtin_convertvector(x, bf16x4);
+    *reinterpret_cast<bf16x4*>(dV + koff + dcol) = __builtin_convertvector(y, bf16x4);
+}
+
+hipError_t launch_bwd_acc_finish(const Dims& D, const float* accK, const float* accV, void* dK, void* dV, hipStream_t st) {
+    const int64_t rows = int64_t(D.B) * D.Hkv * D.n;
+    LRSA_TIMED_LAUNCH("k_bwd_acc_finish", st, k_bwd_acc_finish, dim3((unsigned)((rows + 7) / 8)), dim3(256), 0, st, D, accK,
+                      accV, (bf16_t*)dK, (bf16_t*)dV);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------ launcher
 hipError_t launch_attn_bwd_mfma(const Dims& D, const void* Q, const void* K, const void* V, const void* O,
                                 const void* dO, const float* lse, const int32_t* idx, void* dQ, void* dK,
-                                void* dV, void* ws, hipStream_t st) {
+                                void* dV, float* accK, float* accV, void* ws, hipStream_t st) {
     const BwdPlan P = make_plan(D);
-    float* Dsum = reinterpret_cast<float*>(ws);
-    float* lse2 = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + P.off_lse2);
+    // D and lse in log2 units hold the rows of the window only; like the caller's tensors they are addressed by
+    // absolute row, hence the shifted bases
+    float* Dsum = reinterpret_cast<float*>(ws) - D.row_begin;
+    float* lse2 = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + P.off_lse2) - D.row_begin;
     float* part = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + P.off_part);
     const bf16_t *q = (const bf16_t*)Q, *k = (const bf16_t*)K, *v = (const bf16_t*)V, *o = (const bf16_t*)O,
                  *g = (const bf16_t*)dO;
 
+    const bool compact = D.compact && P.gl_total > 0;
+    const bf16_t *kc = nullptr, *vc = nullptr;
     {
         const int gh = heads_per_wg(D);
         const QTileMap M = make_qtile_map(D, gh, DQ_WAVES);
         const int64_t wgs = int64_t(D.B) * D.Hkv * M.per_unit;
-        const bool compact = D.compact && P.gl_total > 0;
-        const bf16_t *kc = nullptr, *vc = nullptr;
         if (compact && wgs > 0) {
             kc = reinterpret_cast<const bf16_t*>(reinterpret_cast<const char*>(ws) + P.off_compact);
             vc = reinterpret_cast<const bf16_t*>(reinterpret_cast<const char*>(ws) + P.off_compact + compact_kv_bytes(D) / 2);
@@ -818,15 +907,22 @@ hipError_t launch_attn_bwd_mfma(const Dims& D, const void* Q, const void* K, con
         }
 #undef LRSA_DQ_LAUNCH
     }
-    const int ktiles = P.sink_tiles_k + D.nq * P.tpc_k;
-    const int64_t wgs = int64_t(P.gather_wgs) + int64_t(D.B) * D.Hkv * ktiles;
+    const int64_t wgs = int64_t(P.gather_wgs) + int64_t(D.B) * D.Hkv * P.ktiles;
     if (wgs > 0)
-        LRSA_TIMED_LAUNCH("k_bwd_dkv", st, k_bwd_dkv, dim3((unsigned)wgs), dim3(KV_THREADS), 0, st, D, q, k, v, g, lse2,
-                          Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, part, P);
+        LRSA_TIMED_LAUNCH("k_bwd_dkv", st, k_bwd_dkv, dim3((unsigned)wgs), dim3(KV_THREADS), 0, st, D, q, k, v, kc, vc, g,
+                          lse2, Dsum, idx, (bf16_t*)dK, (bf16_t*)dV, accK, accV, part, P);
     const int64_t entries = int64_t(D.B) * D.Hkv * P.gl_total;
+    float *dkc = nullptr, *dvc = nullptr;
+    if (compact) {
+        dkc = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + P.off_dkc);
+        dvc = dkc + align256(size_t(entries) * 128 * 4) / 4;
+    }
     if (entries > 0)
         LRSA_TIMED_LAUNCH("k_bwd_dkv_reduce", st, k_bwd_dkv_reduce, dim3((unsigned)((entries + 7) / 8)), dim3(256), 0, st, D,
-                          idx, part, (bf16_t*)dK, (bf16_t*)dV, P);
+                          idx, part, (bf16_t*)dK, (bf16_t*)dV, accK, accV, dkc, dvc, P);
+    if (entries > 0 && compact)
+        LRSA_TIMED_LAUNCH("k_bwd_scatter_dkv", st, k_bwd_scatter_dkv, dim3((unsigned)((entries + 7) / 8)), dim3(256), 0, st, D,
+                          idx, dkc, dvc, (bf16_t*)dK, (bf16_t*)dV, P.gl_total);
     return hipGetLastError();
 }
 

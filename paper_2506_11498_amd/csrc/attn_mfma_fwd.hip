@@ -313,7 +313,7 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
                 const bf16x4 pk = __builtin_convertvector(v, bf16x4);
                 *reinterpret_cast<bf16x4*>(orow + db * 32 + a * 8 + g * 4) = pk;
             }
-        if (g == 0) lse[(int64_t(b) * D.Hq + hq) * D.n + tq] = (st.m_run + __builtin_log2f(l_tot)) * 0.6931471805599453f;
+        if (g == 0) lse[(int64_t(b) * D.Hq + hq) * D.lse_stride + tq] = (st.m_run + __builtin_log2f(l_tot)) * 0.6931471805599453f;
     }
 }
 

@@ -15,6 +15,11 @@ struct Dims {
     int dtype;  // 0 fp32, 1 bf16
     int compact;  // MFMA attention kernels read a condensed copy of the gather list's K/V rows
     int64_t qs[3], ks[3];
+    // Attention over a window of query rows (one "filling" step of m chunks): rows [row_begin, row_end), which
+    // are the query chunks [fq0, fq1) plus the sink rows when row_begin == 0.  The whole sequence by default.
+    int row_begin, row_end, fq0, fq1;
+    int64_t lse_stride;   // floats between the lse (and D) rows of consecutive (batch, query head) pairs
+    int acc;              // backward adds dK, dV into fp32 accumulators instead of writing them
 };
 
 // Number of entries of the gather list "sink ++ survivors of chunks 0..c-1" and the first
@@ -63,7 +68,8 @@ hipError_t launch_attn_fwd_mfma(const Dims&, const void* Q, const void* K, const
 size_t attn_bwd_mfma_ws_bytes(const Dims&);
 hipError_t launch_attn_bwd_mfma(const Dims&, const void* Q, const void* K, const void* V, const void* O,
                                 const void* dO, const float* lse, const int32_t* idx, void* dQ, void* dK,
-                                void* dV, void* ws, hipStream_t st);
+                                void* dV, float* accK, float* accV, void* ws, hipStream_t st);
+hipError_t launch_bwd_acc_finish(const Dims&, const float* accK, const float* accV, void* dK, void* dV, hipStream_t st);
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 

@@ -232,6 +232,7 @@ __device__ __forceinline__ int stream_pos(const Dims& D, const int32_t* idx_h, i
 // keeps serving the K/V rows of the same head.
 struct QTileMap {
     int sink_tiles, tpc, tiles;   // query tiles of QT rows: in the sink, per chunk, per head
+    int tix_lo, tix_hi;           // the tiles that are launched (all of them unless a row window is set)
     int gsubs, per_unit, xcd_map;
 };
 __device__ __forceinline__ void decode_qtile(const QTileMap& M, const Dims& D, int i, int& b, int& h, int& gsub,
@@ -248,7 +249,7 @@ __device__ __forceinline__ void decode_qtile(const QTileMap& M, const Dims& D, i
     b = unit / D.Hkv;
     h = unit % D.Hkv;
     gsub = w % M.gsubs;
-    tix = M.tiles - 1 - w / M.gsubs;   // heaviest (latest) query tile first
+    tix = M.tix_hi - 1 - w / M.gsubs;   // heaviest (latest) query tile first
 }
 
 // ---- condensed KV cache --------------------------------------------------------------------------
@@ -276,8 +277,10 @@ inline QTileMap make_qtile_map(const Dims& D, int gh, int waves) {
     M.sink_tiles = (sink_rows + qt - 1) / qt;
     M.tpc = (D.L + qt - 1) / qt;
     M.tiles = M.sink_tiles + D.nq * M.tpc;
+    M.tix_lo = D.row_begin == 0 ? 0 : M.sink_tiles + D.fq0 * M.tpc;
+    M.tix_hi = M.sink_tiles + D.fq1 * M.tpc;
     M.gsubs = D.G / gh;
-    M.per_unit = M.tiles * M.gsubs;
+    M.per_unit = (M.tix_hi - M.tix_lo) * M.gsubs;
     M.xcd_map = (D.B * D.Hkv) % 8 == 0 ? 1 : 0;
     return M;
 }

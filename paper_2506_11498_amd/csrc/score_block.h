@@ -32,6 +32,39 @@ __device__ __forceinline__ float row16_sum(float v) {
     return v;
 }
 
+// Eq. 7-8 given the standard deviations: max-subtracted softmax of sig0 over the L tokens, the same for sig1,
+// their sum written to sig0[r] (and to out[r] when out is not null).  sig0, sig1: LDS, L floats each, complete
+// and visible to the NT threads of the block on entry; sm: NT/64 floats of LDS.  Each thread touches only rows
+// r = tid, tid + NT, ...: callers that read other rows afterwards synchronise first.
+template <int NT>
+__device__ __forceinline__ void softmax_sum_block(float* sig0, const float* sig1, float* sm, int L,
+                                                  float* __restrict__ out) {
+    constexpr int NW = NT / 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    auto block_red = [&](float v, bool is_max) {
+        v = is_max ? wave_max(v) : wave_sum(v);
+        __syncthreads();
+        if (lane == 0) sm[wave] = v;
+        __syncthreads();
+        float r = sm[0];
+        for (int i = 1; i < NW; ++i) r = is_max ? fmaxf(r, sm[i]) : r + sm[i];
+        return r;
+    };
+    float mk = -INFINITY, mv = -INFINITY;
+    for (int r = tid; r < L; r += NT) { mk = fmaxf(mk, sig0[r]); mv = fmaxf(mv, sig1[r]); }
+    mk = block_red(mk, true);
+    mv = block_red(mv, true);
+    float zk = 0.0f, zv = 0.0f;
+    for (int r = tid; r < L; r += NT) { zk += expf(sig0[r] - mk); zv += expf(sig1[r] - mv); }
+    zk = block_red(zk, false);
+    zv = block_red(zv, false);
+    for (int r = tid; r < L; r += NT) {
+        const float sc = expf(sig0[r] - mk) / zk + expf(sig1[r] - mv) / zv;
+        if (out) out[r] = sc;
+        sig0[r] = sc;     // each thread overwrites only what it alone has read
+    }
+}
+
 template <typename T>
 __device__ __forceinline__ void score_chunk_block(int L, int d, int ddof, const T* __restrict__ Kcur,
                                                   const T* __restrict__ Kref, const T* __restrict__ Vcur,
@@ -165,28 +198,7 @@ __device__ __forceinline__ void score_chunk_block(int L, int d, int ddof, const 
         __syncthreads();
     }
     // ---- phase 3
-    auto block_red = [&](float v, bool is_max) {
-        v = is_max ? wave_max(v) : wave_sum(v);
-        __syncthreads();
-        if (lane == 0) sh.sm[wave] = v;
-        __syncthreads();
-        float r = sh.sm[0];
-        for (int i = 1; i < NW; ++i) r = is_max ? fmaxf(r, sh.sm[i]) : r + sh.sm[i];
-        return r;
-    };
-    float mk = -INFINITY, mv = -INFINITY;
-    for (int r = tid; r < L; r += FUSED_THREADS) { mk = fmaxf(mk, sh.sig[0][r]); mv = fmaxf(mv, sh.sig[1][r]); }
-    mk = block_red(mk, true);
-    mv = block_red(mv, true);
-    float zk = 0.0f, zv = 0.0f;
-    for (int r = tid; r < L; r += FUSED_THREADS) { zk += expf(sh.sig[0][r] - mk); zv += expf(sh.sig[1][r] - mv); }
-    zk = block_red(zk, false);
-    zv = block_red(zv, false);
-    for (int r = tid; r < L; r += FUSED_THREADS) {
-        const float sc = expf(sh.sig[0][r] - mk) / zk + expf(sh.sig[1][r] - mv) / zv;
-        if (out) out[r] = sc;
-        sh.sig[0][r] = sc;     // each thread overwrites only what it alone has read
-    }
+    softmax_sum_block<FUSED_THREADS>(sh.sig[0], sh.sig[1], sh.sm, L, out);
 }
 
 }  // namespace lrsa
