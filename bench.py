@@ -222,13 +222,18 @@ def main():
             counters = json.load(open(cpath)).get(f"{dom}:{w.name}")
         roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic, "counters": counters, "avg_launch_ms": kern_ms[dom],
-                    "algorithmic_flop_per_launch": kern_flops[dom]}
+                    "algorithmic_flop_per_launch": kern_flops[dom],
+                    # achieved / frac / avg_launch_ms are measured by this run; traffic and counters are NOT:
+                    # they are read from the committed rocprofv3 --pmc summaries of the same command
+                    "traffic_source": "profiles/traffic.json (committed rocprofv3 --pmc runs, not this run)",
+                    "counters_source": "profiles/counters.json (committed rocprofv3 --pmc runs, not this run)"}
 
     def stage(names):
         return sum(kern_ms.get(k, 0.0) * launches.get(k, 0.0) for k in names)
     esz = 2 if w.dtype == "bf16" else 4
     score_bytes = 2 * w.B * w.Hkv * w.n * w.d * esz + 4 * w.B * w.Hkv * Ns * w.L
-    ms_score = stage(["k_score_select_fused", "k_score_fused", "k_minmaxT", "k_sigmaT", "k_softmax"])
+    ms_score = stage(["k_score_select_fused", "k_score_fused", "k_score_stream", "k_softmax_select", "k_minmaxT", "k_sigmaT",
+                      "k_softmax"])
     ms_select = stage(["k_select"])
     ms_fwd = stage(["k_fwd_mfma", "k_fwd_genericT"])      # k_compact_kv runs in both calls: counted below
     ms_bwd = stage(["k_bwd_dq", "k_bwd_dkv", "k_bwd_dkv_reduce", "k_bwd_dq_genericT", "k_bwd_dkv_genericT",

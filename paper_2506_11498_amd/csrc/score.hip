@@ -207,6 +207,8 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_score_fused(Dims D, const T* 
 template <typename T>
 static hipError_t run_score(const Dims& D, const void* K, const void* V, float* score, int32_t* idx, void* ws,
                             hipStream_t st) {
+    if (score_stream_applies(D))      // bf16, head_dim 128, enough streams to fill the chip: one read of K and V
+        return launch_score_stream(D, K, V, score, idx, reinterpret_cast<float*>(ws), st);
     if (D.L <= FUSED_MAX_L) {
         if (idx)
             LRSA_TIMED_LAUNCH("k_score_select_fused", st, (k_score_fused<T, true>), dim3(D.Ns, D.B * D.Hkv), dim3(FUSED_THREADS),
