@@ -109,11 +109,15 @@ int lrsa_score(const lrsa_params *p, const void *K, const void *V, float *score,
 int lrsa_select(const lrsa_params *p, const float *score, int32_t *idx,
                 void *ws, size_t ws_bytes, void *stream);
 
-/* lrsa_score followed by lrsa_select in one call, and in one launch where the chunk fits the fused
- * kernel: the workgroup that has just scored a chunk (Eq. 4-8) takes its top K while the scores are
- * still in LDS (text after Eq. 8).  Writes exactly what the two calls would write: score and idx are
- * bit-identical to theirs.  Arguments as in lrsa_score and lrsa_select; the workspace is the one of
- * lrsa_score (LRSA_WS_SCORE).  Ns == 0 is legal: nothing is written. */
+/* lrsa_score followed by lrsa_select in one call: the kernel that finishes the scores of a chunk
+ * (Eq. 4-8) takes its top K while they are still in LDS (text after Eq. 8), so no selection launch
+ * and no second read of the scores is needed (one to three launches, depending on the shape).  Writes
+ * exactly what the two calls would write: score and idx are bit-identical to theirs.  Arguments as in
+ * lrsa_score and lrsa_select; the workspace is the one of lrsa_score (LRSA_WS_SCORE).  Ns == 0 is
+ * legal: nothing is written.
+ * For bf16 with head_dim 128 and many (batch, KV head) pairs the scoring kernels keep small hint
+ * words in device memory that the library owns; calls that score on the same GPU at the same time
+ * (different streams or threads) may overwrite each other's hints, which costs time, never results. */
 int lrsa_score_select(const lrsa_params *p, const void *K, const void *V, float *score, int32_t *idx,
                       void *ws, size_t ws_bytes, void *stream);
 

@@ -39,6 +39,7 @@ __host__ __device__ inline int window_start(const Dims& D, int q) {
 size_t score_ws_bytes(const Dims&);
 hipError_t launch_score(const Dims&, const void* K, const void* V, float* score, void* ws, hipStream_t st);
 
+hipError_t launch_softmax_select(const Dims&, const float* sigma, float* score, int32_t* idx, hipStream_t st);
 bool score_stream_applies(const Dims&);
 hipError_t launch_score_stream(const Dims&, const void* K, const void* V, float* score, int32_t* idx, float* sigma,
                                hipStream_t st);

@@ -4,10 +4,13 @@
 // chunk p): per-channel min / max over the rows of the reference chunk p+1 (Eq. 4-5), rows of chunk p
 // normalised by them (Eq. 6) and their standard deviation over the channels, then the softmax over the
 // chunk's tokens for K and for V, summed (Eq. 7-8); optionally the top-K selection of the chunk right away.
-// Longer chunks: three launches through the workspace,
-//   k_minmax   per-channel min / max over a slice of the rows of the reference chunk p+1
-//   k_sigma    rows of chunk p normalised by the combined min / max, Std over channels
-//   k_softmax  Softmax over the L tokens of the chunk for K and for V, summed
+// Longer chunks, and shapes with so few (batch, KV head, chunk) units that one workgroup each would leave more
+// than half of the CUs idle: three launches through the workspace, the rows of a chunk cut into slices of 256,
+//   k_minmax          per-channel min / max over a slice of the rows of the reference chunk p+1
+//   k_sigma           rows of chunk p normalised by the combined min / max, Std over channels
+//   k_softmax_select  Softmax over the L tokens of the chunk for K and for V, summed; optionally the top K
+// (chunks beyond 4096 tokens: k_softmax, then the stand-alone selection kernel).
+// Shapes with many (batch, KV head) streams go to the streaming kernel (score_stream.hip) instead.
 // All arithmetic is fp32 on the stored values with correctly rounded division and square root, two-pass
 // variance, max-subtracted softmax.  Rows are read with 16-byte loads, a row being spread over
 // consecutive lanes so that a wave reads whole rows back to back.
@@ -50,11 +53,15 @@ __global__ __launch_bounds__(SCORE_THREADS) void k_minmax(Dims D, const T* __res
     float mn[VEC], mx[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; ++i) { mn[i] = INFINITY; mx[i] = -INFINITY; }
-    for (int r = r0 + rg; r < r1; r += rpp) {
-        float v[VEC];
-        Elem<T>::load(Z + (base + r) * D.ks[2] + lane * VEC, v);
+    for (int r = r0 + rg; r < r1; r += 4 * rpp) {       // four loads in flight; a row past the slice repeats row r
+        float v[4][VEC];
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) { mn[i] = fminf(mn[i], v[i]); mx[i] = fmaxf(mx[i], v[i]); }
+        for (int j = 0; j < 4; ++j)
+            Elem<T>::load(Z + (base + (r + j * rpp < r1 ? r + j * rpp : r)) * D.ks[2] + lane * VEC, v[j]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) { mn[i] = fminf(mn[i], v[j][i]); mx[i] = fmaxf(mx[i], v[j][i]); }
     }
     __shared__ float smn[SCORE_THREADS * 8], smx[SCORE_THREADS * 8];
 #pragma unroll
@@ -95,43 +102,76 @@ __global__ __launch_bounds__(SCORE_THREADS) void k_sigma(Dims D, const T* __rest
     const int lane = threadIdx.x % lpr, rg = threadIdx.x / lpr;
     const int64_t unit = (int64_t(bh) * 2 + z) * D.Ns + p;
 
-    // combine the partial min / max of the reference chunk for this thread's channels
-    float mn[VEC], den[VEC];
-    {
-        const float* src = mm + unit * nsplit * 2 * D.d;
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) {
-            const int c = lane * VEC + i;
-            float a = INFINITY, m = -INFINITY;
-            for (int s = 0; s < nsplit; ++s) {
-                a = fminf(a, src[s * 2 * D.d + c]);
-                m = fmaxf(m, src[s * 2 * D.d + D.d + c]);
-            }
-            mn[i] = a;
-            const float dd = m - a;
-            den[i] = dd == 0.0f ? 1.0f : dd;
+    // combine the partial min / max of the reference chunk: thread t reduces entry t of the 2 * d floats of a
+    // partial (coalesced, the loads of different partials independent of each other), then every thread picks
+    // up its own channels from LDS
+    __shared__ float s_mm[2 * 128];
+    if (threadIdx.x < 2 * D.d) {
+        const float* src = mm + unit * nsplit * 2 * D.d + threadIdx.x;
+        const bool is_min = threadIdx.x < D.d;
+        float a = is_min ? INFINITY : -INFINITY;
+#pragma unroll 4
+        for (int s = 0; s < nsplit; ++s) {
+            const float x = src[int64_t(s) * 2 * D.d];
+            a = is_min ? fminf(a, x) : fmaxf(a, x);
         }
+        s_mm[threadIdx.x] = a;
     }
-    // the lanes of one row leave the loop together, so the shuffles below stay among active lanes
-    for (int r = r0 + rg; r < r1; r += rpp) {
-        float v[VEC];
-        Elem<T>::load(Z + (base + r) * D.ks[2] + lane * VEC, v);
-        float s = 0.0f;
+    __syncthreads();
+    float mn[VEC], den[VEC], inv[VEC];
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) {
-            v[i] = (v[i] - mn[i]) / den[i];
-            s += v[i];
-        }
-        for (int o = lpr >> 1; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-        const float mean = s / float(D.d);
-        float q = 0.0f;
+    for (int i = 0; i < VEC; ++i) {
+        const int c = lane * VEC + i;
+        mn[i] = s_mm[c];
+        const float dd = s_mm[D.d + c] - mn[i];
+        den[i] = dd == 0.0f ? 1.0f : dd;
+        inv[i] = 1.0f / den[i];
+    }
+    const float inv_d = 1.0f / float(D.d), inv_dof = 1.0f / float(D.d - D.ddof);
+    // Four rows per thread and iteration, so that four loads are in flight; a row past the slice repeats the
+    // slice's last row of this thread and is not stored.  The lanes of one row run the same iterations, so
+    // the shuffles stay among active lanes.  The quotient of Eq. 6 is the reciprocal product with one fused
+    // residual correction, which reproduces the IEEE quotient.
+    for (int r = r0 + rg; r < r1; r += 4 * rpp) {
+        float v[4][VEC], s[4], q[4];
+        int rr[4];
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) {
-            const float dv = v[i] - mean;
-            q += dv * dv;
+        for (int j = 0; j < 4; ++j) {
+            rr[j] = r + j * rpp < r1 ? r + j * rpp : r;
+            Elem<T>::load(Z + (base + rr[j]) * D.ks[2] + lane * VEC, v[j]);
         }
-        for (int o = lpr >> 1; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
-        if (lane == 0) sigma[unit * D.L + r] = sqrtf(q / float(D.d - D.ddof));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                const float a0 = v[j][i] - mn[i];
+                float q0 = a0 * inv[i];
+                q0 = __builtin_fmaf(__builtin_fmaf(-den[i], q0, a0), inv[i], q0);
+                v[j][i] = q0;
+                acc += q0;
+            }
+            s[j] = acc;
+        }
+        for (int o = lpr >> 1; o > 0; o >>= 1)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s[j] += __shfl_xor(s[j], o, 64);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float mean = s[j] * inv_d;
+            float acc = 0.0f;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) { const float dv = v[j][i] - mean; acc += dv * dv; }
+            q[j] = acc;
+        }
+        for (int o = lpr >> 1; o > 0; o >>= 1)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) q[j] += __shfl_xor(q[j], o, 64);
+        if (lane == 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (j == 0 || r + j * rpp < r1) sigma[unit * D.L + rr[j]] = sqrtf(q[j] * inv_dof);
+        }
     }
 }
 
@@ -209,7 +249,10 @@ static hipError_t run_score(const Dims& D, const void* K, const void* V, float* 
                             hipStream_t st) {
     if (score_stream_applies(D))      // bf16, head_dim 128, enough streams to fill the chip: one read of K and V
         return launch_score_stream(D, K, V, score, idx, reinterpret_cast<float*>(ws), st);
-    if (D.L <= FUSED_MAX_L) {
+    // one workgroup per (batch, KV head, chunk) would leave more than half of the CUs idle, and the chunks are
+    // long enough to be cut into slices: the three-launch path below spreads them over 8 * L / 1024 times as many
+    const bool few_units = int64_t(D.Ns) * D.B * D.Hkv * 2 <= 256 && score_splits(D.L) >= 4;
+    if (D.L <= FUSED_MAX_L && !few_units) {
         if (idx)
             LRSA_TIMED_LAUNCH("k_score_select_fused", st, (k_score_fused<T, true>), dim3(D.Ns, D.B * D.Hkv), dim3(FUSED_THREADS),
                               0, st, D, (const T*)K, (const T*)V, score, idx);
@@ -223,6 +266,7 @@ static hipError_t run_score(const Dims& D, const void* K, const void* V, float* 
     const dim3 grid(score_splits(D.L), D.Ns, D.B * D.Hkv * 2);
     LRSA_TIMED_LAUNCH("k_minmaxT", st, k_minmax<T>, grid, dim3(SCORE_THREADS), 0, st, D, (const T*)K, (const T*)V, mm);
     LRSA_TIMED_LAUNCH("k_sigmaT", st, k_sigma<T>, grid, dim3(SCORE_THREADS), 0, st, D, (const T*)K, (const T*)V, mm, sigma);
+    if (D.L <= FUSED_MAX_L) return launch_softmax_select(D, sigma, score, idx, st);
     LRSA_TIMED_LAUNCH("k_softmax", st, k_softmax, dim3(D.Ns, D.B * D.Hkv), dim3(SCORE_THREADS), 0, st, D, sigma, score);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && idx) e = launch_select(D, score, idx, nullptr, st);

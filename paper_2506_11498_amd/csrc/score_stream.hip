@@ -644,6 +644,18 @@ hipError_t device_state(DeviceState* out) {
 }
 }  // namespace
 
+// Eq. 7-8 (and the selection when idx is given) from standard deviations that other kernels left in `sigma`
+hipError_t launch_softmax_select(const Dims& D, const float* sigma, float* score, int32_t* idx, hipStream_t st) {
+    const size_t sx_lds = size_t(2) * D.L * sizeof(float);
+    if (idx)
+        LRSA_TIMED_LAUNCH("k_softmax_select", st, k_softmax_select<true>, dim3(D.Ns, D.B * D.Hkv), dim3(SX_THREADS), sx_lds, st,
+                          D, sigma, score, idx, (mail_t*)nullptr, 0);
+    else
+        LRSA_TIMED_LAUNCH("k_softmax", st, k_softmax_select<false>, dim3(D.Ns, D.B * D.Hkv), dim3(SX_THREADS), sx_lds, st, D,
+                          sigma, score, idx, (mail_t*)nullptr, 0);
+    return hipGetLastError();
+}
+
 bool score_stream_applies(const Dims& D) { return make_stream_plan(D, SS_MAX_WGS).use != 0; }
 
 // scores (and, with idx, the selection) through the streaming kernel; sigma: B * Hkv * 2 * Ns * L floats of workspace

@@ -2,10 +2,14 @@
 // largest score, ties to the lowest position, written ascending.
 //
 // Scores are positive floats, so their bit patterns order like unsigned integers.  The workgroup finds
-// the bit pattern of the K-th largest score with a 4-pass, 8-bit radix select (histogram in LDS, suffix
-// scan over the 256 buckets), then compacts in position order: every score above the threshold, plus the
-// first `need` scores equal to it.  All integer work, hence deterministic.  Used by the stand-alone
-// selection kernel (keys in global memory) and by the fused scoring kernel (keys in LDS).
+// the bit pattern of the K-th largest score with an 8-bit radix select (histogram in LDS, suffix scan over
+// the 256 buckets), then compacts in position order: every score above the threshold, plus the first
+// `need` scores equal to it.  The scores of one chunk share their sign and most of their exponent, so the
+// digits are taken from (pattern - smallest pattern of the chunk), shifted left until the span's top bit is
+// bit 31: the first histogram then spreads over the buckets instead of piling its LDS atomics on one or two
+// addresses, and a narrow span needs fewer than four passes.  The map is monotone and one-to-one, so the
+// order, the ties and hence the selection are unchanged.  All integer work, hence deterministic.  Used by
+// the stand-alone selection kernel (keys in global memory) and by the scoring kernels (keys in LDS).
 #pragma once
 #include "common.h"
 
@@ -47,14 +51,41 @@ template <int NT>
 __device__ __forceinline__ void select_topk_block(const uint32_t* key, int L, int K, int base, int32_t* out,
                                                   SelectLds& sh) {
     static_assert(NT >= 256 && NT % 64 == 0 && NT <= 1024, "block size");
-    const int tid = threadIdx.x, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int NW = NT / 64;
+    // smallest and largest pattern of the chunk
+    uint32_t lo = 0xffffffffu, hi = 0u;
+    for (int r = tid; r < L; r += NT) {
+        const uint32_t k = key[r];
+        lo = k < lo ? k : lo;
+        hi = k > hi ? k : hi;
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t a = uint32_t(__shfl_xor(int(lo), o, 64)), b = uint32_t(__shfl_xor(int(hi), o, 64));
+        lo = a < lo ? a : lo;
+        hi = b > hi ? b : hi;
+    }
+    if (lane == 0) { sh.hist[wave] = int(lo); sh.hist[NW + wave] = int(hi); }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        const uint32_t a = uint32_t(sh.hist[i]), b = uint32_t(sh.hist[NW + i]);
+        lo = a < lo ? a : lo;
+        hi = b > hi ? b : hi;
+    }
+    __syncthreads();      // the histogram is cleared next
+    const uint32_t span = hi - lo;
+    const int lsh = span ? __builtin_clz(span) : 31;            // (k - lo) << lsh puts the span's top bit at bit 31
+    const int low_zero = lsh >> 3;                              // low bytes that are zero for every key: no pass
+    auto rel = [&](uint32_t k) { return (k - lo) << lsh; };
     uint32_t prefix = 0, mask = 0;
     int need = K;  // how many of the elements matching `prefix` on the decided bytes are still wanted
-    for (int shift = 24; shift >= 0; shift -= 8) {
+    for (int shift = 24; shift >= 8 * low_zero; shift -= 8) {
         if (tid < 256) sh.hist[tid] = 0;
         __syncthreads();
         for (int r = tid; r < L; r += NT) {
-            const uint32_t k = key[r];
+            const uint32_t k = rel(key[r]);
             if ((k & mask) == prefix) atomicAdd(&sh.hist[(k >> shift) & 255], 1);
         }
         __syncthreads();
@@ -85,12 +116,12 @@ __device__ __forceinline__ void select_topk_block(const uint32_t* key, int L, in
         need = sh.need;
         mask |= 0xffu << shift;
     }
-    // prefix is now the K-th largest bit pattern; `need` of the elements equal to it are taken.  One packed
+    // prefix is now the K-th largest (shifted) pattern; `need` of the elements equal to it are taken.  One packed
     // scan per NT elements: larger ones in the low half-word, equal ones in the high half-word.
     int gt_seen = 0, eq_seen = 0;
     for (int r0 = 0; r0 < L; r0 += NT) {
         const int r = r0 + tid;
-        const uint32_t k = r < L ? key[r] : 0u;
+        const uint32_t k = r < L ? rel(key[r]) : 0u;
         const int is_gt = (r < L && k > prefix) ? 1 : 0;
         const int is_eq = (r < L && k == prefix) ? 1 : 0;
         int total;

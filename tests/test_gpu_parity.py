@@ -165,19 +165,39 @@ def test_select_is_exact_on_heavily_tied_scores():
     assert np.array_equal(got, ref.select(sc, w.S, w.L, w.K))
 
 
+# Which kernels score a shape is the library's choice; each case names the ones it is meant to exercise and the
+# test checks, through the library's kernel timers, that they are the ones that ran.
+ONE_WG = {"k_score_select_fused"}                             # one workgroup per (batch, KV head, chunk)
+SLICED = {"k_minmaxT", "k_sigmaT", "k_softmax_select"}        # few units: chunks cut into slices of 256 rows
+LONG = {"k_minmaxT", "k_sigmaT", "k_softmax", "k_select"}     # chunks beyond 4096 tokens
+
+
 @pytest.mark.parametrize("cfg", [
-    dict(n=3 + 9 * 300 + 5, L=300, S=3, K=77, d=64, Hq=2, Hkv=2, B=2, dtype="f32"),           # ragged L, fp32
-    dict(n=16 + 6 * 1024 + 100, L=1024, S=16, K=256, d=128, Hq=2, Hkv=2, B=1, dtype="bf16"),   # one key per thread
-    dict(n=8 + 4 * 4096 + 9, L=4096, S=8, K=1000, d=128, Hq=1, Hkv=1, B=1, dtype="bf16"),     # largest fused chunk
-    dict(n=8 + 3 * 4100 + 9, L=4100, S=8, K=17, d=128, Hq=1, Hkv=1, B=1, dtype="bf16"),       # beyond it: two launches
-    dict(n=40, L=32, S=64, K=8, d=128, Hq=1, Hkv=1, B=1, dtype="bf16"),                       # nothing to score
-], ids=["f32_ragged", "bf16_L1024", "bf16_L4096", "bf16_L4100_fallback", "no_chunks"])
+    dict(n=3 + 9 * 300 + 5, L=300, S=3, K=77, d=64, Hq=2, Hkv=2, B=2, dtype="f32", kernels=ONE_WG),       # ragged L, fp32
+    dict(n=16 + 6 * 640 + 100, L=640, S=16, K=256, d=128, Hq=2, Hkv=2, B=1, dtype="bf16", kernels=ONE_WG),
+    dict(n=16 + 6 * 1024 + 100, L=1024, S=16, K=256, d=128, Hq=2, Hkv=2, B=1, dtype="bf16", kernels=SLICED),
+    dict(n=5 + 4 * 1000 + 77, L=1000, S=5, K=100, d=64, Hq=2, Hkv=1, B=2, dtype="f32", kernels=SLICED),   # ragged last slice
+    dict(n=8 + 4 * 4096 + 9, L=4096, S=8, K=1000, d=128, Hq=1, Hkv=1, B=1, dtype="bf16", kernels=SLICED),
+    # largest chunk of the one-workgroup kernel (four rows per thread); enough heads that it is the one chosen
+    dict(n=8 + 5 * 4096 + 9, L=4096, S=8, K=1000, d=128, Hq=33, Hkv=33, B=1, dtype="bf16", kernels=ONE_WG),
+    dict(n=8 + 3 * 4100 + 9, L=4100, S=8, K=17, d=128, Hq=1, Hkv=1, B=1, dtype="bf16", kernels=LONG),
+    dict(n=40, L=32, S=64, K=8, d=128, Hq=1, Hkv=1, B=1, dtype="bf16", kernels=set()),                    # nothing to score
+], ids=["f32_ragged", "bf16_L640", "bf16_L1024_sliced", "f32_L1000_sliced", "bf16_L4096_sliced", "bf16_L4096_one_wg",
+        "bf16_L4100_long", "no_chunks"])
 def test_fused_score_select_equals_the_two_calls_and_the_oracle(cfg):
+    cfg = dict(cfg)
+    kernels = cfg.pop("kernels")
     w = inputs.small_workload(**cfg)
     x = inputs.make_inputs(w)
     xd = {k: v.to(DEV) for k, v in x.items()}
     p, score, idx = run_score_select(w, xd)
-    score_f, idx_f = lrsa.lrsa_score_select(p, xd["K"], xd["V"])
+    lrsa.timing_enable(True)
+    try:
+        score_f, idx_f = lrsa.lrsa_score_select(p, xd["K"], xd["V"])
+        torch.cuda.synchronize()
+        assert {k for k, _ in lrsa.timing_records()} == kernels
+    finally:
+        lrsa.timing_enable(False)
     assert torch.equal(score_f, score) and torch.equal(idx_f, idx)      # bit-identical to the two calls
     if lrsa.num_scored_chunks(p):
         xf = {k: v.float().numpy() for k, v in x.items()}
