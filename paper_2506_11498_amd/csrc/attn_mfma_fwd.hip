@@ -85,6 +85,16 @@ __device__ __forceinline__ void fwd_tile(const unsigned char* sK, const unsigned
             }
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) s[1] = mfma32(a1[kk], qf[kk], s[1]);
+            // keep the order written above -- 8 operand reads, then one read per MFMA, then 8 MFMAs: left alone,
+            // the compiler moves every read down to just before its MFMA to save registers, and the MFMA then
+            // waits out the whole LDS latency (0x100: LDS reads, 0x008: MFMAs)
+            __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
         } else {
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) s[0] = mfma32(a[kk], qf[kk], s[0]);
