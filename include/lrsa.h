@@ -121,6 +121,14 @@ int lrsa_select(const lrsa_params *p, const float *score, int32_t *idx,
 int lrsa_score_select(const lrsa_params *p, const void *K, const void *V, float *score, int32_t *idx,
                       void *ws, size_t ws_bytes, void *stream);
 
+/* Debug aid for callers that bring their own idx (text after Eq. 8 fixes what a valid selection is): counts
+ * the rows (b, h, p) of idx that break the precondition of the attention calls -- K positions inside chunk p,
+ * [S+pL, S+(p+1)L), strictly ascending -- which those calls do not check.
+ *   idx      : [B, Hkv, Ns, K] int32, contiguous; may be NULL when Ns == 0          (device, read)
+ *   bad_rows : one int32; receives the number of offending rows, 0 for a valid idx   (device, written)
+ * Enqueued on `stream` like every call; read bad_rows after synchronising. */
+int lrsa_check_idx(const lrsa_params *p, const int32_t *idx, int32_t *bad_rows, void *stream);
+
 /* Attention forward, Eq. 2-3 under the chunked mask: O[t] = sum_u softmax_u(scale q_t.k_u) v_u over
  * the keys u <= t that are in the sink, in the local window of t's chunk, or listed in idx;
  * lse[t] = log sum_u exp(scale q_t.k_u).  Query head hq reads KV head hq / G.

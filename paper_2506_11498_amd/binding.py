@@ -20,7 +20,7 @@ IMPL_AUTO, IMPL_GENERIC, IMPL_COMPACT = 0, 1, 2
 WS_SCORE, WS_SELECT, WS_ATTN_FWD, WS_ATTN_BWD, WS_DECODE_ATTN = 0, 1, 2, 3, 4
 
 EXPORTS = ("lrsa_abi_version", "lrsa_last_error", "lrsa_num_scored_chunks", "lrsa_workspace_bytes",
-           "lrsa_score", "lrsa_select", "lrsa_score_select", "lrsa_attn_fwd", "lrsa_attn_bwd",
+           "lrsa_score", "lrsa_select", "lrsa_score_select", "lrsa_check_idx", "lrsa_attn_fwd", "lrsa_attn_bwd",
            "lrsa_cache_compress", "lrsa_decode_attn", "lrsa_decode_attn_static",
            "lrsa_fill_workspace_bytes", "lrsa_attn_fwd_fill", "lrsa_attn_bwd_fill", "lrsa_attn_bwd_finish",
            "lrsa_timing_enable", "lrsa_timing_count", "lrsa_timing_read")
@@ -63,6 +63,7 @@ def lib() -> ctypes.CDLL:
         L.lrsa_score.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.lrsa_select.argtypes = [vp, vp, vp, vp, sz, vp]
         L.lrsa_score_select.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
+        L.lrsa_check_idx.argtypes = [vp, vp, vp, vp]
         L.lrsa_cache_compress.argtypes = [vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp]
         L.lrsa_decode_attn.argtypes = [vp, vp, vp, vp, ctypes.c_int32, vp, vp, vp, sz, vp]
         L.lrsa_decode_attn_static.argtypes = [vp, vp, vp, vp, ctypes.c_int32, vp, vp, vp]
@@ -191,6 +192,20 @@ def lrsa_select(p: LrsaParams, score: torch.Tensor, idx: Optional[torch.Tensor] 
     ws, nb = _workspace(p, WS_SELECT, score.device, ws)
     _check(lib().lrsa_select(ctypes.byref(p), _ptr(score), _ptr(idx), _ptr(ws), nb, _stream()))
     return idx
+
+
+def lrsa_check_idx(p: LrsaParams, idx: Optional[torch.Tensor], bad_rows: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Number of rows of idx that are not K ascending positions of their chunk, as a device int32 tensor of one
+    element (0 for a valid idx).  Enqueued like every call: `.item()` on the result synchronises."""
+    Ns = num_scored_chunks(p)
+    device = idx.device if idx is not None else torch.device("cuda", torch.cuda.current_device())
+    if idx is not None:
+        _expect("idx", idx, (p.batch, p.heads_kv, Ns, p.topk), None, torch.int32, device)
+    if bad_rows is None:
+        bad_rows = torch.empty(1, dtype=torch.int32, device=device)
+    _expect("bad_rows", bad_rows, (1,), None, torch.int32, device)
+    _check(lib().lrsa_check_idx(ctypes.byref(p), _ptr(idx), _ptr(bad_rows), _stream()))
+    return bad_rows
 
 
 def lrsa_score_select(p: LrsaParams, K: torch.Tensor, V: torch.Tensor, score: Optional[torch.Tensor] = None,

@@ -143,6 +143,15 @@ int lrsa_select(const lrsa_params* p, const float* score, int32_t* idx, void* ws
     return hip_result(lrsa::launch_select(D, score, idx, ws, (hipStream_t)stream), "lrsa_select");
 }
 
+int lrsa_check_idx(const lrsa_params* p, const int32_t* idx, int32_t* bad_rows, void* stream) {
+    lrsa::Dims D;
+    int rc = make_dims(p, &D);
+    if (rc != LRSA_OK) return rc;
+    if (!bad_rows) return fail(LRSA_ERR_INVALID_ARG, "lrsa_check_idx: bad_rows must not be NULL");
+    if (D.Ns > 0 && !idx) return fail(LRSA_ERR_INVALID_ARG, "lrsa_check_idx: idx must not be NULL");
+    return hip_result(lrsa::launch_check_idx(D, idx, bad_rows, (hipStream_t)stream), "lrsa_check_idx");
+}
+
 int lrsa_score_select(const lrsa_params* p, const void* K, const void* V, float* score, int32_t* idx, void* ws,
                       size_t ws_bytes, void* stream) {
     lrsa::Dims D;

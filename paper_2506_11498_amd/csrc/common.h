@@ -46,6 +46,7 @@ hipError_t launch_score_stream(const Dims&, const void* K, const void* V, float*
 
 size_t select_ws_bytes(const Dims&);
 hipError_t launch_select(const Dims&, const float* score, int32_t* idx, void* ws, hipStream_t st);
+hipError_t launch_check_idx(const Dims&, const int32_t* idx, int32_t* bad_rows, hipStream_t st);
 size_t decode_ws_bytes(const Dims&);
 bool cache_compress_supported(const Dims&);
 hipError_t launch_cache_compress(const Dims&, void* Kc, void* Vc, int32_t* pos, int len, int done, int steps, hipStream_t st);

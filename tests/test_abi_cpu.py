@@ -90,6 +90,9 @@ def test_null_pointers_and_small_workspace_fail_before_any_gpu_work():
     assert rc == -1 and b"aligned" in L.lrsa_last_error()
     rc = L.lrsa_select(ctypes.byref(p), None, None, None, 0, None)
     assert rc == -1
+    fake = ctypes.c_void_p(4096)
+    assert L.lrsa_check_idx(ctypes.byref(p), fake, None, None) == -1 and b"bad_rows" in L.lrsa_last_error()
+    assert L.lrsa_check_idx(ctypes.byref(p), None, fake, None) == -1 and b"idx" in L.lrsa_last_error()
 
 
 def test_no_compressed_chunks_is_a_legal_noop_for_score_and_select():

@@ -154,6 +154,21 @@ def test_uniform_chunk_ties_go_to_lowest_positions():
     assert list(idx.cpu().numpy()[0, 0, 1]) == list(range(w.S + w.L, w.S + w.L + w.K))
 
 
+def test_check_idx_counts_the_rows_that_break_the_precondition():
+    w = inputs.small_workload(n=8 + 7 * 64 + 9, L=64, S=8, K=16, d=128, Hq=4, Hkv=2, B=2, dtype="bf16")
+    x = inputs.make_inputs(w)
+    xd = {k: v.to(DEV) for k, v in x.items()}
+    p, _, idx = run_score_select(w, xd)
+    assert lrsa.lrsa_check_idx(p, idx).item() == 0
+    bad = idx.clone()
+    bad[0, 0, 1, 3] = bad[0, 0, 1, 2]            # not strictly ascending
+    bad[1, 1, 4, 15] = w.S + 5 * w.L             # first position of the NEXT chunk
+    bad[1, 0, 0, 0] = w.S - 1                    # a sink position
+    assert lrsa.lrsa_check_idx(p, bad).item() == 3
+    bad[1, 0, 0, 1] = -7                         # a second fault in an already bad row: rows are counted, not entries
+    assert lrsa.lrsa_check_idx(p, bad).item() == 3
+
+
 def test_select_is_exact_on_heavily_tied_scores():
     rng = np.random.default_rng(5)
     w = inputs.small_workload(n=3 + 9 * 300 + 5, L=300, S=3, K=77, d=64, Hq=2, Hkv=2, B=2)
@@ -168,21 +183,22 @@ def test_select_is_exact_on_heavily_tied_scores():
 # Which kernels score a shape is the library's choice; each case names the ones it is meant to exercise and the
 # test checks, through the library's kernel timers, that they are the ones that ran.
 ONE_WG = {"k_score_select_fused"}                             # one workgroup per (batch, KV head, chunk)
-SLICED = {"k_minmaxT", "k_sigmaT", "k_softmax_select"}        # few units: chunks cut into slices of 256 rows
+SLICED = {"k_minmaxT", "k_sigmaT", "k_softmax_select"}        # few units of long chunks: cut into slices of 256 rows
 LONG = {"k_minmaxT", "k_sigmaT", "k_softmax", "k_select"}     # chunks beyond 4096 tokens
 
 
 @pytest.mark.parametrize("cfg", [
     dict(n=3 + 9 * 300 + 5, L=300, S=3, K=77, d=64, Hq=2, Hkv=2, B=2, dtype="f32", kernels=ONE_WG),       # ragged L, fp32
     dict(n=16 + 6 * 640 + 100, L=640, S=16, K=256, d=128, Hq=2, Hkv=2, B=1, dtype="bf16", kernels=ONE_WG),
-    dict(n=16 + 6 * 1024 + 100, L=1024, S=16, K=256, d=128, Hq=2, Hkv=2, B=1, dtype="bf16", kernels=SLICED),
-    dict(n=5 + 4 * 1000 + 77, L=1000, S=5, K=100, d=64, Hq=2, Hkv=1, B=2, dtype="f32", kernels=SLICED),   # ragged last slice
+    dict(n=16 + 6 * 1024 + 100, L=1024, S=16, K=256, d=128, Hq=2, Hkv=2, B=1, dtype="bf16", kernels=ONE_WG),   # one key per thread
+    dict(n=16 + 4 * 2048 + 100, L=2048, S=16, K=512, d=128, Hq=2, Hkv=2, B=1, dtype="bf16", kernels=SLICED),
+    dict(n=5 + 4 * 2000 + 77, L=2000, S=5, K=100, d=64, Hq=2, Hkv=1, B=2, dtype="f32", kernels=SLICED),   # ragged last slice
     dict(n=8 + 4 * 4096 + 9, L=4096, S=8, K=1000, d=128, Hq=1, Hkv=1, B=1, dtype="bf16", kernels=SLICED),
     # largest chunk of the one-workgroup kernel (four rows per thread); enough heads that it is the one chosen
     dict(n=8 + 5 * 4096 + 9, L=4096, S=8, K=1000, d=128, Hq=33, Hkv=33, B=1, dtype="bf16", kernels=ONE_WG),
     dict(n=8 + 3 * 4100 + 9, L=4100, S=8, K=17, d=128, Hq=1, Hkv=1, B=1, dtype="bf16", kernels=LONG),
     dict(n=40, L=32, S=64, K=8, d=128, Hq=1, Hkv=1, B=1, dtype="bf16", kernels=set()),                    # nothing to score
-], ids=["f32_ragged", "bf16_L640", "bf16_L1024_sliced", "f32_L1000_sliced", "bf16_L4096_sliced", "bf16_L4096_one_wg",
+], ids=["f32_ragged", "bf16_L640", "bf16_L1024", "bf16_L2048_sliced", "f32_L2000_sliced", "bf16_L4096_sliced", "bf16_L4096_one_wg",
         "bf16_L4100_long", "no_chunks"])
 def test_fused_score_select_equals_the_two_calls_and_the_oracle(cfg):
     cfg = dict(cfg)
