@@ -94,6 +94,56 @@ def test_filling_steps_equal_one_shot_and_oracle(cfg, m, local_prev):
     assert rel(dV.float().cpu().numpy(), g[2]) < 2e-2
 
 
+def test_filling_steps_at_full_size_C4_equal_the_one_shot_call():
+    """The headline workload (32K tokens, 32/8 heads) in steps of 4 chunks, with the library's own selection:
+    O, lse and dQ bit for bit, dK and dV within 2e-3 of the one-shot call (which the full-size parity tests hold
+    against the oracle); the step-wise schedule's time and workspace are printed beside the one-shot call's."""
+    w = inputs.WORKLOADS["C4"]
+    xd = {k: v.to(DEV) for k, v in inputs.make_inputs(w).items()}
+    p = lrsa.params_for(xd["Q"], xd["K"], sink=w.S, lag=w.L, topk=w.K)
+    _, idx = lrsa.lrsa_score_select(p, xd["K"], xd["V"])
+    O1, lse1 = lrsa.lrsa_attn_fwd(p, xd["Q"], xd["K"], xd["V"], idx)
+    dQ1, dK1, dV1 = lrsa.lrsa_attn_bwd(p, xd["Q"], xd["K"], xd["V"], O1, xd["dO"], lse1, idx)
+    torch.cuda.synchronize()
+    m = 4
+    steps = windows(w, m)
+    O = torch.empty_like(O1); lse = torch.empty_like(lse1); dQ = torch.empty_like(dQ1)
+    accK = torch.zeros(xd["K"].shape, dtype=torch.float32, device=DEV)
+    accV = torch.zeros_like(accK)
+    dK, dV = torch.empty_like(xd["K"]), torch.empty_like(xd["K"])
+    params = {}
+    for a, b in steps:
+        pf = lrsa.params_for(xd["Q"][:, :, a:b], xd["K"], sink=w.S, lag=w.L, topk=w.K)   # Q, O, dO, dQ rows as views
+        pf.seq = w.n
+        params[(a, b)] = pf
+    ws = torch.empty(max(max(lrsa.fill_workspace_bytes(params[s_], s_[0], s_[1], k) for s_ in steps) for k in (2, 3)) + 256,
+                     dtype=torch.uint8, device=DEV)
+    lse_rows = {s_: torch.empty((w.B, w.Hq, s_[1] - s_[0]), dtype=torch.float32, device=DEV) for s_ in steps}   # contiguous per step
+    for timed in (False, True):          # the first pass warms the allocator and the code objects up
+        accK.zero_(); accV.zero_()
+        t0, t1, t2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        t0.record()
+        for a, b in steps:
+            lrsa.lrsa_attn_fwd_fill(params[(a, b)], a, b, xd["Q"][:, :, a:b], xd["K"], xd["V"], idx, O[:, :, a:b], lse_rows[(a, b)], ws)
+        t1.record()
+        for a, b in reversed(steps):
+            lrsa.lrsa_attn_bwd_fill(params[(a, b)], a, b, xd["Q"][:, :, a:b], xd["K"], xd["V"], O[:, :, a:b], xd["dO"][:, :, a:b],
+                                    lse_rows[(a, b)], idx, accK, accV, dQ[:, :, a:b], ws)
+        lrsa.lrsa_attn_bwd_finish(p, accK, accV, dK, dV)
+        t2.record()
+        torch.cuda.synchronize()
+    for a, b in steps:
+        lse[:, :, a:b] = lse_rows[(a, b)]
+    print(f"C4 in {len(steps)} steps of {m} chunks: forward {t0.elapsed_time(t1):.2f} ms, backward {t1.elapsed_time(t2):.2f} ms "
+          f"(host-driven, includes launch gaps); workspace {ws.numel() / 1e6:.0f} MB + {2 * accK.numel() * 4 / 1e6:.0f} MB of accumulators "
+          f"against {lrsa.workspace_bytes(p, 3) / 1e6:.0f} MB one-shot")
+    assert torch.equal(O, O1) and torch.equal(lse, lse1) and torch.equal(dQ, dQ1)
+    for name, x, r in (("dK", dK, dK1), ("dV", dV, dV1)):
+        x = x.float(); r = r.float()
+        e = max(((x - r).abs().max() / r.abs().max()).item(), ((x - r).norm() / r.norm()).item())
+        assert e < 2e-3, (name, e)
+
+
 def test_fill_rejects_windows_off_the_chunk_grid():
     w = inputs.small_workload(n=16 + 6 * 64 + 40, L=64, S=16, K=16, d=128, Hq=4, Hkv=2, B=1, dtype="bf16")
     xd = {k: v.to(DEV) for k, v in inputs.make_inputs(w).items()}
