@@ -4,9 +4,9 @@
 // chunk p): per-channel min / max over the rows of the reference chunk p+1 (Eq. 4-5), rows of chunk p
 // normalised by them (Eq. 6) and their standard deviation over the channels, then the softmax over the
 // chunk's tokens for K and for V, summed (Eq. 7-8); optionally the top-K selection of the chunk right away.
-// Longer chunks, and shapes with so few (batch, KV head, chunk) units of at least 4 * 256 rows that one workgroup
+// Longer chunks, and shapes with so few (batch, KV head, chunk) units of at least 1024 rows that one workgroup
 // each would leave more than half of the CUs idle: three launches through the workspace, the rows of a chunk cut
-// into slices of 256,
+// into slices of 128 (256 beyond 4096 tokens),
 //   k_minmax          per-channel min / max over a slice of the rows of the reference chunk p+1
 //   k_sigma           rows of chunk p normalised by the combined min / max, Std over channels
 //   k_softmax_select  Softmax over the L tokens of the chunk for K and for V, summed; optionally the top K
@@ -23,7 +23,8 @@ namespace lrsa {
 constexpr int SCORE_THREADS = 256;
 
 // rows of the chunk handled by one workgroup of k_minmax / k_sigma
-__host__ __device__ inline int score_rows_per_wg(int L) { return L < 256 ? L : 256; }
+// (128 where the route is taken to spread few chunks over the chip, 256 for chunks beyond 4096 tokens)
+__host__ __device__ inline int score_rows_per_wg(int L) { return L < 128 ? L : (L <= FUSED_MAX_L ? 128 : 256); }
 __host__ __device__ inline int score_splits(int L) { int r = score_rows_per_wg(L); return (L + r - 1) / r; }
 
 // workspace layout: mm[unit][split][2][d] floats, then sigma[unit][L] floats; unit = ((b*Hkv+h)*2+z)*Ns+p
@@ -251,9 +252,9 @@ static hipError_t run_score(const Dims& D, const void* K, const void* V, float* 
     if (score_stream_applies(D))      // bf16, head_dim 128, enough streams to fill the chip: one read of K and V
         return launch_score_stream(D, K, V, score, idx, reinterpret_cast<float*>(ws), st);
     // one workgroup per (batch, KV head, chunk) would leave more than half of the CUs idle, and the chunks are
-    // long enough (4 slices of 256 rows or more) that three launches over many workgroups beat one launch over
-    // few: measured at 60 units of 1024 rows, 8 + 14 + 10 us of kernel time against 43 us
-    const bool few_units = int64_t(D.Ns) * D.B * D.Hkv * 2 <= 256 && score_splits(D.L) >= 4;
+    // long enough (1024 rows or more) that three launches over many workgroups beat one launch over
+    // few: measured at 60 units of 1024 rows, 8 + 11 + 9 us of kernel time against 43 us
+    const bool few_units = int64_t(D.Ns) * D.B * D.Hkv * 2 <= 256 && D.L >= 1024;
     if (D.L <= FUSED_MAX_L && !few_units) {
         if (idx)
             LRSA_TIMED_LAUNCH("k_score_select_fused", st, (k_score_fused<T, true>), dim3(D.Ns, D.B * D.Hkv), dim3(FUSED_THREADS),

@@ -584,32 +584,44 @@ __global__ __launch_bounds__(SS_THREADS, 1) void k_score_stream(Dims D, const bf
 }
 
 // Softmax over the chunk's tokens for K and V, summed (Eq. 7-8); SELECT: the chunk's top K right away (text after
-// Eq. 8).  One workgroup of SX_THREADS per (batch, KV head, chunk): small workgroups, several per CU, because the
-// work is a chain of short block-wide reductions and scans.  Dynamic LDS: 2 * L floats.  The workgroups also
-// clear the mailbox words that the streaming kernel of this call may have written.
-constexpr int SX_THREADS = 256;
-template <bool SELECT>
-__global__ __launch_bounds__(SX_THREADS) void k_softmax_select(Dims D, const float* __restrict__ sigma,
-                                                               float* __restrict__ score, int32_t* __restrict__ idx,
-                                                               mail_t* mail_part, int part_words) {
+// Eq. 8).  One workgroup of NT threads per (batch, KV head, chunk).  The work is a chain of short block-wide
+// reductions and scans: with many chunks small workgroups (several per CU) finish soonest, with few chunks (fewer
+// than CUs) the chain itself is the time and more threads shorten it.  Dynamic LDS: 2 * L floats.  The workgroups
+// also clear the mailbox words that the streaming kernel of this call may have written.
+template <bool SELECT, int NT>
+__global__ __launch_bounds__(NT) void k_softmax_select(Dims D, const float* __restrict__ sigma, float* __restrict__ score,
+                                                       int32_t* __restrict__ idx, mail_t* mail_part, int part_words) {
     const int p = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
     extern __shared__ float sx_sig[];     // [2][L]
-    __shared__ float sm[SX_THREADS / 64];
+    __shared__ float sm[NT / 64];
     float* sig0 = sx_sig;
     float* sig1 = sx_sig + D.L;
     const float* sk = sigma + ((int64_t(bh) * 2 + 0) * D.Ns + p) * D.L;
     const float* sv = sigma + ((int64_t(bh) * 2 + 1) * D.Ns + p) * D.L;
-    for (int r = tid; r < D.L; r += SX_THREADS) { sig0[r] = sk[r]; sig1[r] = sv[r]; }
+    for (int r = tid; r < D.L; r += NT) { sig0[r] = sk[r]; sig1[r] = sv[r]; }
     __syncthreads();
-    softmax_sum_block<SX_THREADS>(sig0, sig1, sm, D.L, score + (int64_t(bh) * D.Ns + p) * D.L);
+    softmax_sum_block<NT>(sig0, sig1, sm, D.L, score + (int64_t(bh) * D.Ns + p) * D.L);
     if (SELECT) {
         __shared__ SelectLds sel;
         __syncthreads();
-        select_topk_block<SX_THREADS>(reinterpret_cast<const uint32_t*>(sig0), D.L, D.K, D.S + p * D.L,
-                                      idx + (int64_t(bh) * D.Ns + p) * D.K, sel);
+        select_topk_block<NT>(reinterpret_cast<const uint32_t*>(sig0), D.L, D.K, D.S + p * D.L,
+                              idx + (int64_t(bh) * D.Ns + p) * D.K, sel);
     }
     const int64_t g = int64_t(bh) * gridDim.x + p, G = int64_t(gridDim.x) * gridDim.y;
-    for (int64_t e = g * SX_THREADS + tid; e < part_words; e += G * SX_THREADS) mail_part[e] = 0;
+    for (int64_t e = g * NT + tid; e < part_words; e += G * NT) mail_part[e] = 0;
+}
+
+static hipError_t run_softmax_select(const Dims& D, const float* sigma, float* score, int32_t* idx, mail_t* mail,
+                                     int part_words, hipStream_t st) {
+    const size_t lds = size_t(2) * D.L * sizeof(float);
+    const dim3 grid(D.Ns, D.B * D.Hkv);
+    const bool few = int64_t(D.Ns) * D.B * D.Hkv <= 128 && D.L >= 1024;
+#define LRSA_SX(name, SEL, NT_) \
+    LRSA_TIMED_LAUNCH(name, st, (k_softmax_select<SEL, NT_>), grid, dim3(NT_), lds, st, D, sigma, score, idx, mail, part_words)
+    if (idx) { if (few) LRSA_SX("k_softmax_select", true, 1024); else LRSA_SX("k_softmax_select", true, 256); }
+    else { if (few) LRSA_SX("k_softmax", false, 1024); else LRSA_SX("k_softmax", false, 256); }
+#undef LRSA_SX
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------ host side
@@ -646,14 +658,7 @@ hipError_t device_state(DeviceState* out) {
 
 // Eq. 7-8 (and the selection when idx is given) from standard deviations that other kernels left in `sigma`
 hipError_t launch_softmax_select(const Dims& D, const float* sigma, float* score, int32_t* idx, hipStream_t st) {
-    const size_t sx_lds = size_t(2) * D.L * sizeof(float);
-    if (idx)
-        LRSA_TIMED_LAUNCH("k_softmax_select", st, k_softmax_select<true>, dim3(D.Ns, D.B * D.Hkv), dim3(SX_THREADS), sx_lds, st,
-                          D, sigma, score, idx, (mail_t*)nullptr, 0);
-    else
-        LRSA_TIMED_LAUNCH("k_softmax", st, k_softmax_select<false>, dim3(D.Ns, D.B * D.Hkv), dim3(SX_THREADS), sx_lds, st, D,
-                          sigma, score, idx, (mail_t*)nullptr, 0);
-    return hipGetLastError();
+    return run_softmax_select(D, sigma, score, idx, nullptr, 0, st);
 }
 
 bool score_stream_applies(const Dims& D) { return make_stream_plan(D, SS_MAX_WGS).use != 0; }
@@ -673,14 +678,7 @@ hipError_t launch_score_stream(const Dims& D, const void* K, const void* V, floa
         LRSA_TIMED_LAUNCH("k_score_stream", st, (k_score_stream<SS_PF_1, SS_LAG_1>), dim3(P.wgs), dim3(SS_THREADS), 0, st, D,
                           (const bf16_t*)K, (const bf16_t*)V, sigma, ds.part, P, seq << 12);
     const int part_words = P.W > 1 ? P.wgs * SS_NR * 128 : 0;
-    const size_t sx_lds = size_t(2) * D.L * sizeof(float);
-    if (idx)
-        LRSA_TIMED_LAUNCH("k_softmax_select", st, k_softmax_select<true>, dim3(D.Ns, D.B * D.Hkv), dim3(SX_THREADS), sx_lds, st,
-                          D, sigma, score, idx, ds.part, part_words);
-    else
-        LRSA_TIMED_LAUNCH("k_softmax", st, k_softmax_select<false>, dim3(D.Ns, D.B * D.Hkv), dim3(SX_THREADS), sx_lds, st, D,
-                          sigma, score, idx, ds.part, part_words);
-    return hipGetLastError();
+    return run_softmax_select(D, sigma, score, idx, ds.part, part_words, st);
 }
 
 }  // namespace lrsa
