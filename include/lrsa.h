@@ -85,6 +85,13 @@ typedef enum {
 /* Ns of the partition above; pure host arithmetic.  Returns a negative lrsa_status on bad params. */
 int lrsa_num_scored_chunks(const lrsa_params *p);
 
+/* Which kernels lrsa_score / lrsa_score_select use for these params (Eq. 4-8 are the same on every route, the
+ * routes differ in how the rows are spread over the chip); pure host arithmetic, for tests and for reading
+ * profiles.  0: nothing to score (Ns == 0); 1: one workgroup per (batch, KV head, chunk); 2: chunks cut into
+ * row slices, three launches (few, long chunks); 3: one-read streaming kernels (bf16, head_dim 128, many
+ * KV heads); 4: chunks beyond 4096 tokens.  Returns a negative lrsa_status on bad params. */
+int lrsa_score_route(const lrsa_params *p);
+
 /* Bytes of device scratch the call `which` (lrsa_ws_kind) needs for these params; host arithmetic.
  * Returns 0 for bad params (the call itself then reports the error). */
 size_t lrsa_workspace_bytes(const lrsa_params *p, int which);

@@ -115,6 +115,12 @@ int lrsa_num_scored_chunks(const lrsa_params* p) {
     return rc != LRSA_OK ? rc : D.Ns;
 }
 
+int lrsa_score_route(const lrsa_params* p) {
+    lrsa::Dims D;
+    const int rc = make_dims(p, &D);
+    return rc != LRSA_OK ? rc : lrsa::score_route(D);
+}
+
 size_t lrsa_workspace_bytes(const lrsa_params* p, int which) {
     lrsa::Dims D;
     if (make_dims(p, &D) != LRSA_OK) return 0;

@@ -37,6 +37,7 @@ __host__ __device__ inline int window_start(const Dims& D, int q) {
 
 // ---- launchers (each enqueues on `st` and returns the first HIP error) ----------------------
 size_t score_ws_bytes(const Dims&);
+int score_route(const Dims&);
 hipError_t launch_score(const Dims&, const void* K, const void* V, float* score, void* ws, hipStream_t st);
 
 hipError_t launch_softmax_select(const Dims&, const float* sigma, float* score, int32_t* idx, hipStream_t st);

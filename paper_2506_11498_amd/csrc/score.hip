@@ -245,17 +245,27 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_score_fused(Dims D, const T* 
     }
 }
 
-// idx != nullptr: scores AND the selection (one launch when the fused kernel applies, else two)
+// Which kernels score a shape (host arithmetic; the numbers are lrsa_score_route's):
+//   1  one workgroup per (batch, KV head, chunk)
+//   2  sliced: one workgroup per (batch, KV head, chunk) would leave more than half of the CUs idle, and the
+//      chunks are long enough (1024 rows or more) that three launches over many workgroups beat one launch over
+//      few: measured at 60 units of 1024 rows, 8 + 11 + 9 us of kernel time against 43 us
+//   3  streaming: bf16, head_dim 128, enough (batch, KV head) streams to fill the chip: one read of K and V
+//   4  chunks beyond the LDS of the one-workgroup kernel: sliced, with softmax and selection in launches of their own
+int score_route(const Dims& D) {
+    if (D.Ns == 0) return 0;
+    if (score_stream_applies(D)) return 3;
+    if (D.L > FUSED_MAX_L) return 4;
+    return int64_t(D.Ns) * D.B * D.Hkv * 2 <= 256 && D.L >= 1024 ? 2 : 1;
+}
+
+// idx != nullptr: scores AND the selection (taken by the last kernel of the route, except on route 4)
 template <typename T>
 static hipError_t run_score(const Dims& D, const void* K, const void* V, float* score, int32_t* idx, void* ws,
                             hipStream_t st) {
-    if (score_stream_applies(D))      // bf16, head_dim 128, enough streams to fill the chip: one read of K and V
-        return launch_score_stream(D, K, V, score, idx, reinterpret_cast<float*>(ws), st);
-    // one workgroup per (batch, KV head, chunk) would leave more than half of the CUs idle, and the chunks are
-    // long enough (1024 rows or more) that three launches over many workgroups beat one launch over
-    // few: measured at 60 units of 1024 rows, 8 + 11 + 9 us of kernel time against 43 us
-    const bool few_units = int64_t(D.Ns) * D.B * D.Hkv * 2 <= 256 && D.L >= 1024;
-    if (D.L <= FUSED_MAX_L && !few_units) {
+    const int route = score_route(D);
+    if (route == 3) return launch_score_stream(D, K, V, score, idx, reinterpret_cast<float*>(ws), st);
+    if (route == 1) {
         if (idx)
             LRSA_TIMED_LAUNCH("k_score_select_fused", st, (k_score_fused<T, true>), dim3(D.Ns, D.B * D.Hkv), dim3(FUSED_THREADS),
                               0, st, D, (const T*)K, (const T*)V, score, idx);
@@ -269,7 +279,7 @@ static hipError_t run_score(const Dims& D, const void* K, const void* V, float* 
     const dim3 grid(score_splits(D.L), D.Ns, D.B * D.Hkv * 2);
     LRSA_TIMED_LAUNCH("k_minmaxT", st, k_minmax<T>, grid, dim3(SCORE_THREADS), 0, st, D, (const T*)K, (const T*)V, mm);
     LRSA_TIMED_LAUNCH("k_sigmaT", st, k_sigma<T>, grid, dim3(SCORE_THREADS), 0, st, D, (const T*)K, (const T*)V, mm, sigma);
-    if (D.L <= FUSED_MAX_L) return launch_softmax_select(D, sigma, score, idx, st);
+    if (route == 2) return launch_softmax_select(D, sigma, score, idx, st);
     LRSA_TIMED_LAUNCH("k_softmax", st, k_softmax, dim3(D.Ns, D.B * D.Hkv), dim3(SCORE_THREADS), 0, st, D, sigma, score);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && idx) e = launch_select(D, score, idx, nullptr, st);
