@@ -21,7 +21,10 @@ constexpr int FWD_BN = 64;     // keys per tile
 constexpr int FWD_WAVES = 8;   // waves per workgroup (two per SIMD), 32 queries each
 constexpr int FWD_THREADS = 64 * FWD_WAVES;
 
-bool mfma_supported(const Dims& D) { return D.dtype == 1 && D.d == 128; }
+// bf16, head_dim 128, and a head's K/V rows within 2 GiB of its first row (the copies use 32-bit byte offsets)
+bool mfma_supported(const Dims& D) {
+    return D.dtype == 1 && D.d == 128 && int64_t(D.n) * D.ks[2] * 2 < (int64_t(1) << 31);
+}
 size_t attn_fwd_mfma_ws_bytes(const Dims& D) { return compact_kv_bytes(D); }
 
 // Copies the K and V rows of every gather-list entry into the condensed cache: 16 lanes per row, 16 rows
@@ -239,7 +242,8 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
         raw.a4 = smem_load(idx_ld, pos_entry(tc, 4)); raw.a5 = smem_load(idx_ld, pos_entry(tc, 5));
         raw.a6 = smem_load(idx_ld, pos_entry(tc, 6)); raw.a7 = smem_load(idx_ld, pos_entry(tc, 7));
     };
-    auto issue = [&](int tile, Scalar8& raw, unsigned char* sK, unsigned char* sV) {
+    // laK, laV: LDS byte addresses of the stage's K tile and V tile (compile-time constants at the call sites)
+    auto issue = [&](int tile, Scalar8& raw, unsigned laK, unsigned laV) {
         const int tc = tile < ntiles ? tile : ntiles - 1;
         const int q4 = lane >> 4;
         if (!COMPACT) smem_wait(raw);
@@ -249,15 +253,17 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
             int j = tc * FWD_BN + r4 + q4;
             j = j < m_max ? j : m_max - 1;
             const int ch = async_chunk(r4 + q4, lane) * 8;
+            const unsigned row_la = unsigned(r4) * TILE_ROW_BYTES;      // wave-uniform
             if (COMPACT) {
-                async_rows4(stream_row(Kc_h, Kh, D.ks[2], j, ng, cs) + ch, sK, r4);
-                async_rows4(stream_row(Vc_h, Vh, D.ks[2], j, ng, cs) + ch, sV, r4);
+                async_copy16_la(stream_row(Kc_h, Kh, D.ks[2], j, ng, cs) + ch, laK + row_la);
+                async_copy16_la(stream_row(Vc_h, Vh, D.ks[2], j, ng, cs) + ch, laV + row_la);
             } else {
                 const int sel = i == 0 ? pick4(q4, raw.a0, raw.a1, raw.a2, raw.a3) : pick4(q4, raw.a4, raw.a5, raw.a6, raw.a7);
                 const int pos = j < ng ? (j < D.S ? j : sel) : cs + (j - ng);
-                const int64_t off = int64_t(pos) * D.ks[2] + ch;
-                async_rows4(Kh + off, sK, r4);
-                async_rows4(Vh + off, sV, r4);
+                // byte offset inside the head: below 2^31 (a condition of this kernel, checked on the host)
+                const unsigned off = (unsigned(pos) * unsigned(D.ks[2]) + unsigned(ch)) * 2u;
+                async_copy16_so(Kh, off, laK + row_la);
+                async_copy16_so(Vh, off, laV + row_la);
             }
         }
     };
@@ -283,27 +289,28 @@ __global__ __launch_bounds__(FWD_THREADS, 2) void k_fwd_mfma(Dims D, const bf16_
     // A wave's vector memory operations in order:  A(0) A(1) A(2) | iteration t: A(t+3)   (A = the copies
     // of a tile).  At the top of iteration t the operations issued after A(t) are A(t+1) A(t+2).
     Scalar8 posA, posB;
-    fetch_pos(0, posA); issue(0, posA, sT0, sT0 + TILE_BYTES);
-    fetch_pos(1, posB); issue(1, posB, sT1, sT1 + TILE_BYTES);
-    fetch_pos(2, posA); issue(2, posA, sT2, sT2 + TILE_BYTES);
+    const unsigned la0 = lds_addr(sT0), la1 = lds_addr(sT1), la2 = lds_addr(sT2), la3 = lds_addr(sT3);
+    fetch_pos(0, posA); issue(0, posA, la0, la0 + TILE_BYTES);
+    fetch_pos(1, posB); issue(1, posB, la1, la1 + TILE_BYTES);
+    fetch_pos(2, posA); issue(2, posA, la2, la2 + TILE_BYTES);
     fetch_pos(3, posB);
     wait_all_vmem_known();   // the Q fragments (and the first tiles) are here
-#define LRSA_FWD_STEP(t_, sT, sTn, pos_use, pos_fetch)                                               \
+#define LRSA_FWD_STEP(t_, sT, laN, pos_use, pos_fetch)                                               \
     {                                                                                                \
         wait_vmcnt<2 * OPS_PER_TILE>();   /* this wave's copies for tile t_ have landed */            \
         ring_barrier();                   /* everybody's have; everybody is done with tile t_-1 */   \
-        fetch_pos((t_) + 4, pos_fetch);                                                              \
-        issue((t_) + 3, pos_use, sTn, sTn + TILE_BYTES); /* tile t_+3 into the stage tile t_-1 used */ \
+        issue((t_) + 3, pos_use, laN, laN + TILE_BYTES); /* tile t_+3 into the stage tile t_-1 used */ \
+        fetch_pos((t_) + 4, pos_fetch);   /* after the copies: their wait for positions is for ALL scalar loads */ \
         LRSA_FWD_TILE(sT, sT + TILE_BYTES, (t_) * FWD_BN);                                           \
     }
     for (int tile = 0; tile < ntiles; tile += 4) {
-        LRSA_FWD_STEP(tile, sT0, sT3, posB, posA);
+        LRSA_FWD_STEP(tile, sT0, la3, posB, posA);
         if (tile + 1 >= ntiles) break;
-        LRSA_FWD_STEP(tile + 1, sT1, sT0, posA, posB);
+        LRSA_FWD_STEP(tile + 1, sT1, la0, posA, posB);
         if (tile + 2 >= ntiles) break;
-        LRSA_FWD_STEP(tile + 2, sT2, sT1, posB, posA);
+        LRSA_FWD_STEP(tile + 2, sT2, la1, posB, posA);
         if (tile + 3 >= ntiles) break;
-        LRSA_FWD_STEP(tile + 3, sT3, sT2, posA, posB);
+        LRSA_FWD_STEP(tile + 3, sT3, la2, posA, posB);
     }
 #undef LRSA_FWD_STEP
     wait_vmcnt<0>();   // copies issued past the end must land before the workgroup's LDS is released

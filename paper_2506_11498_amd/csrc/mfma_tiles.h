@@ -157,6 +157,26 @@ __device__ __forceinline__ void async_copy4(const void* src, const void* lds_dst
         : "v"(src), "s"(la)
         : "memory");
 }
+// The same copy with the global address given as a wave-uniform base (scalar registers) plus this lane's unsigned
+// 32-bit byte offset, and the LDS destination as a wave-uniform byte address: no 64-bit vector arithmetic and no
+// pointer conversion per copy.  The caller guarantees offsets below 4 GiB.
+__device__ __forceinline__ void async_copy16_so(const void* base, unsigned voff, unsigned lds_byte_addr) {
+    unsigned keep;
+    asm volatile(
+        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
+        : "=&s"(keep)
+        : "v"(voff), "s"(base), "s"(lds_byte_addr)
+        : "memory");
+}
+// ... and with a per-lane 64-bit global address (rows that come from two different buffers)
+__device__ __forceinline__ void async_copy16_la(const void* src, unsigned lds_byte_addr) {
+    unsigned keep;
+    asm volatile(
+        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+        : "=&s"(keep)
+        : "v"(src), "s"(lds_byte_addr)
+        : "memory");
+}
 // src: this lane's 16 bytes in global memory; tile: LDS tile base; r4: first of the 4 rows (wave-uniform)
 __device__ __forceinline__ void async_rows4(const void* src, unsigned char* tile, int r4) {
     async_copy16(src, tile + r4 * TILE_ROW_BYTES);
@@ -192,12 +212,9 @@ __device__ __forceinline__ int smem_load(const int32_t* base, int index) {
 }
 // eight scalars (no array: indexing a private array invites the compiler to move it to memory)
 struct Scalar8 { int a0, a1, a2, a3, a4, a5, a6, a7; };
-// waits for all outstanding scalar loads (and LDS reads); ties the 8 values to the wait
+// waits for all outstanding scalar loads (and LDS reads); ties the 8 values to the wait (they are scalar
+// registers already: the loads' outputs)
 __device__ __forceinline__ void smem_wait(Scalar8& v) {
-    v.a0 = __builtin_amdgcn_readfirstlane(v.a0); v.a1 = __builtin_amdgcn_readfirstlane(v.a1);   // wave-uniform:
-    v.a2 = __builtin_amdgcn_readfirstlane(v.a2); v.a3 = __builtin_amdgcn_readfirstlane(v.a3);   // stay scalar
-    v.a4 = __builtin_amdgcn_readfirstlane(v.a4); v.a5 = __builtin_amdgcn_readfirstlane(v.a5);
-    v.a6 = __builtin_amdgcn_readfirstlane(v.a6); v.a7 = __builtin_amdgcn_readfirstlane(v.a7);
     asm volatile("s_waitcnt lgkmcnt(0)"
                  : "+s"(v.a0), "+s"(v.a1), "+s"(v.a2), "+s"(v.a3), "+s"(v.a4), "+s"(v.a5), "+s"(v.a6), "+s"(v.a7)
                  :
