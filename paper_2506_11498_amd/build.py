@@ -42,6 +42,38 @@ def _check_scratch(remarks: str, src: str) -> None:
                 raise RuntimeError(f"{src}: kernel {name} spills {m.group(1)} bytes/lane to scratch (limit {limit})")
 
 
+# Scalar loads issued from inline assembly (smem_load in mfma_tiles.h) land behind the compiler's back.  If it
+# sees their result as unused it reuses the destination register at once, and if it copies the result before the
+# kernel's own wait the copy is stale; either way a kernel could compute an address from garbage.  So the
+# generated assembly of every source that uses them is scanned: between such a load and the next
+# `s_waitcnt lgkmcnt(0)` (text order) no other instruction may touch the load's destination register.
+def _check_scalar_loads(src: str) -> None:
+    asm = os.path.join(OBJ, os.path.basename(src) + ".s")
+    r = subprocess.run([HIPCC, *FLAGS, "-S", "--cuda-device-only", src, "-o", asm], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc -S failed on {src}")
+    ins = [(i, t.strip()) for i, t in enumerate(open(asm).read().split("\n")) if t.strip() and not t.strip().startswith(";")]
+    for k, (i, t) in enumerate(ins):
+        m = re.match(r"s_load_dword (s\d+),", t)
+        if not m:
+            continue
+        dest = m.group(1)
+        for j, u in ins[k + 1:k + 600]:
+            if "lgkmcnt(0)" in u:
+                break
+            if u.startswith("."):
+                continue
+            ops = u.split(None, 1)
+            if len(ops) < 2:
+                continue
+            used = set()
+            for a, b, c in re.findall(r"\bs\[(\d+):(\d+)\]|\b(s\d+)\b", ops[1]):
+                used.update([c] if c else [f"s{n}" for n in range(int(a), int(b) + 1)])
+            if dest in used:
+                raise RuntimeError(f"{src}: line {i + 1} of {asm}: `{t}` -- {dest} is touched by `{u}` (line {j + 1}) "
+                                   f"before the load is waited for")
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.basename(src) + ".o")
     cmd = [HIPCC, *FLAGS, "-Rpass-analysis=kernel-resource-usage", "-c", src, "-o", obj]
@@ -52,6 +84,8 @@ def _compile(src: str) -> str:
         raise RuntimeError(f"hipcc failed on {src}:\n" + "\n".join(l for l in r.stderr.splitlines() if noise not in l and "remark:" not in l))
     err = "\n".join(l for l in r.stderr.splitlines() if "warning:" in l and noise not in l)
     _check_scratch("\n".join(remarks), src)
+    if "smem_load(" in open(src).read():
+        _check_scalar_loads(src)
     if err.strip():
         sys.stderr.write(err + "\n")
     return obj
