@@ -144,10 +144,7 @@ struct MinMax8 {   // running min / max of 8 channels (one 16-byte piece of a ro
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// one mailbox word
-__device__ __forceinline__ mail_t mail_word(uint32_t tag, uint32_t mn16, uint32_t mx16) {
-    return (mail_t(tag) << 32) | mail_t((mx16 << 16) | (mn16 & 0xffffu));
-}
+// one mailbox word {tag : 32, max : bf16, min : bf16} is written as a single 8-byte store
 __device__ __forceinline__ void mail_store(mail_t* p, mail_t v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -247,9 +244,6 @@ __global__ __launch_bounds__(SS_THREADS, 1) void k_score_stream(Dims D, const bf
         int c, j, slot;
     };
     Cursor ld = {p1, 0, 0};                       // next block to copy in
-    // First row (within the slice's chunk) of block j.  A slice of at least one block: the last block is moved
-    // back so that it ends with the slice (rows it shares with the block before are scored twice, to the same
-    // values); a shorter slice: one block, rows past the slice repeat its last row.
     // First row (within the slice) of block j.  A slice of at least one block: the last block is moved back so
     // that it ends with the slice (rows it shares with the block before are scored twice, to the same values);
     // a shorter slice: one block, rows past the slice repeat its last row.
