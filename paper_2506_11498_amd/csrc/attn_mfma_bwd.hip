@@ -277,7 +277,7 @@ __global__ __launch_bounds__(DQ_THREADS, 2) void k_bwd_dq(Dims D, const bf16_t* 
         for (int i = 0; i < 8; ++i) Dq = __builtin_fmaf(float(o8[i]), float(gf[kk][i]), Dq);
     }
     Dq += __shfl_xor(Dq, 32, 64);
-    if (tq <= t_last && g == 0) { Dsum[rowid] = Dq; lse2_out[rowid] = lse2; }
+    if (tq <= t_last && g == 0) { Dsum[rowid] = -Dq; lse2_out[rowid] = lse2; }   // -D: the key-outer kernel starts its dA sums from it
     const int lim = ng + tq - cs;
     const int wave_lim_max = ng + min(t0 + wq * 32 + 31, t_last) - cs;
 
@@ -370,8 +370,8 @@ __device__ __forceinline__ int first_chunk_seeing(const Dims& D, int j0) {
 }
 
 // One sub-step (32 query rows: rows rowbase .. rowbase+31 of the stage tiles) of the key-outer walk for
-// one wave.  sLD holds this wave's copy of the stage rows' lse in log2 units (floats 0..KV_ROWS-1) and D
-// (the next KV_ROWS floats).  r0 = first row of the sub-step; rows >= tb are padding.
+// one wave.  sLD holds this wave's copy of the stage rows' lse in log2 units (floats 0..KV_ROWS-1) and -D
+// (the next KV_ROWS floats; D = rowsum(dO * O), negated by the query-outer kernel that wrote it).  r0 = first row of the sub-step; rows >= tb are padding.
 // lim_u: GATHER (steps never straddle a chunk): the largest gather-list entry the step's chunk sees.
 // The wave's K fragments are in registers, its V rows in LDS (sVw): K fragments and the accumulators
 // fill the register file.
@@ -397,10 +397,19 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
     // an operand read from the Q / dO stage serves all key blocks of the wave.
     bf16x8 a[2];
     f32x16 s[KV_NB], dp[KV_NB];
+    // dA - D comes out of the MFMAs themselves: the accumulators start from -D of their rows (sLD holds -D)
+#pragma unroll
+    for (int a4 = 0; a4 < 4; ++a4) {
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(sLD + KV_ROWS + rowbase + 8 * a4 + 4 * g);
+#pragma unroll
+        for (int nb = 0; nb < KV_NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dp[nb][a4 * 4 + r] = d4[r];
+    }
 #pragma unroll
     for (int nb = 0; nb < KV_NB; ++nb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) { s[nb][i] = 0.0f; dp[nb][i] = 0.0f; }
+        for (int i = 0; i < 16; ++i) s[nb][i] = 0.0f;
     a[0] = read_rows_a(aQr, 0);
     a[1] = read_rows_a(aQr, 1);
 #pragma unroll
@@ -455,7 +464,7 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
     bf16x8 pf[KV_NB][2], dsf[KV_NB][2];
 #pragma unroll
     for (int nb = 0; nb < KV_NB; ++nb) { pf[nb][0] = pack8(s[nb], 0); pf[nb][1] = pack8(s[nb], 8); }
-    // dV^T += dO^T A (rows 0-15 blocks 0..3, rows 16-31 blocks 0..3) with dS = A * (dA - D) beside it,
+    // dV^T += dO^T A (rows 0-15 blocks 0..3, rows 16-31 blocks 0..3) with dS = A * (dA - D) beside it (dp holds dA - D),
     // then dK^T += Q^T dS in the same order
 #define LRSA_OPND(n) ((n) < 8 ? read_cols_a(aGc, ((n) >> 2) * 16, (n) & 3) : read_cols_a(aQc, (((n) - 8) >> 2) * 16, (n) & 3))
 #pragma unroll
@@ -465,11 +474,10 @@ __device__ __forceinline__ void dkv_step(const Dims& D, const unsigned char* sQ,
         a[n & 1] = LRSA_OPND(n + 2);
         if ((n & 1) == 0) {
             const int a4 = n >> 1;
-            const f32x4 d4 = *reinterpret_cast<const f32x4*>(sLD + KV_ROWS + rowbase + 8 * a4 + 4 * g);
 #pragma unroll
             for (int nb = 0; nb < KV_NB; ++nb)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) dp[nb][a4 * 4 + r] = s[nb][a4 * 4 + r] * (dp[nb][a4 * 4 + r] - d4[r]);
+                for (int r = 0; r < 4; ++r) dp[nb][a4 * 4 + r] *= s[nb][a4 * 4 + r];
         }
     }
 #pragma unroll
