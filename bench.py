@@ -232,7 +232,7 @@ def main():
         return sum(kern_ms.get(k, 0.0) * launches.get(k, 0.0) for k in names)
     esz = 2 if w.dtype == "bf16" else 4
     score_bytes = 2 * w.B * w.Hkv * w.n * w.d * esz + 4 * w.B * w.Hkv * Ns * w.L
-    ms_score = stage(["k_score_select_fused", "k_score_fused", "k_score_stream", "k_softmax_select", "k_minmaxT", "k_sigmaT",
+    ms_score = stage(["k_score_select_fused", "k_score_fused", "k_score_resident", "k_softmax_select", "k_minmaxT", "k_sigmaT",
                       "k_softmax"])
     ms_select = stage(["k_select"])
     ms_fwd = stage(["k_fwd_mfma", "k_fwd_genericT"])      # k_compact_kv runs in both calls: counted below

@@ -88,9 +88,18 @@ int lrsa_num_scored_chunks(const lrsa_params *p);
 /* Which kernels lrsa_score / lrsa_score_select use for these params (Eq. 4-8 are the same on every route, the
  * routes differ in how the rows are spread over the chip); pure host arithmetic, for tests and for reading
  * profiles.  0: nothing to score (Ns == 0); 1: one workgroup per (batch, KV head, chunk); 2: chunks cut into
- * row slices, three launches (few, long chunks); 3: one-read streaming kernels (bf16, head_dim 128, many
- * KV heads); 4: chunks beyond 4096 tokens.  Returns a negative lrsa_status on bad params. */
+ * row slices, three launches (few, long chunks); 3: the one-read kernel, which keeps the rows in registers
+ * from their min / max to their scores (bf16, head_dim 128, chunks of 64 to 4096 rows); 4: chunks beyond
+ * 4096 tokens.  Returns a negative lrsa_status on bad params. */
 int lrsa_score_route(const lrsa_params *p);
+
+/* On route 3 a scoring workgroup takes the min / max of its reference chunk (Eq. 4-5) from hint words that
+ * the workgroups of that chunk publish; `polls` is how many times it looks for them before it computes
+ * these min / max from the rows themselves (a second read of the chunk).  Default 4096; 0: never wait (every
+ * chunk is read twice).  Scores and selections are the same bits for every value: the setting trades time
+ * only.  Process-wide, takes effect with the next call; negative: change nothing.  Returns the previous
+ * value. */
+int lrsa_score_poll_limit(int polls);
 
 /* Bytes of device scratch the call `which` (lrsa_ws_kind) needs for these params; host arithmetic.
  * Returns 0 for bad params (the call itself then reports the error). */
@@ -122,9 +131,9 @@ int lrsa_select(const lrsa_params *p, const float *score, int32_t *idx,
  * exactly what the two calls would write: score and idx are bit-identical to theirs.  Arguments as in
  * lrsa_score and lrsa_select; the workspace is the one of lrsa_score (LRSA_WS_SCORE).  Ns == 0 is
  * legal: nothing is written.
- * For bf16 with head_dim 128 and many (batch, KV head) pairs the scoring kernels keep small hint
- * words in device memory that the library owns; calls that score on the same GPU at the same time
- * (different streams or threads) may overwrite each other's hints, which costs time, never results. */
+ * On route 3 (lrsa_score_route; lrsa_score takes it too) the scoring kernel keeps small hint words in 8 MB
+ * of device memory that the library owns; calls that score on the same GPU at the same time (different
+ * streams or threads) may overwrite each other's hints, which costs time, never results. */
 int lrsa_score_select(const lrsa_params *p, const void *K, const void *V, float *score, int32_t *idx,
                       void *ws, size_t ws_bytes, void *stream);
 

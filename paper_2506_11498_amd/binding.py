@@ -19,7 +19,7 @@ LRSA_F32, LRSA_BF16 = 0, 1
 IMPL_AUTO, IMPL_GENERIC, IMPL_COMPACT = 0, 1, 2
 WS_SCORE, WS_SELECT, WS_ATTN_FWD, WS_ATTN_BWD, WS_DECODE_ATTN = 0, 1, 2, 3, 4
 
-EXPORTS = ("lrsa_abi_version", "lrsa_last_error", "lrsa_num_scored_chunks", "lrsa_score_route", "lrsa_workspace_bytes",
+EXPORTS = ("lrsa_abi_version", "lrsa_last_error", "lrsa_num_scored_chunks", "lrsa_score_route", "lrsa_score_poll_limit", "lrsa_workspace_bytes",
            "lrsa_score", "lrsa_select", "lrsa_score_select", "lrsa_check_idx", "lrsa_attn_fwd", "lrsa_attn_bwd",
            "lrsa_cache_compress", "lrsa_decode_attn", "lrsa_decode_attn_static",
            "lrsa_fill_workspace_bytes", "lrsa_attn_fwd_fill", "lrsa_attn_bwd_fill", "lrsa_attn_bwd_finish",
@@ -60,6 +60,8 @@ def lib() -> ctypes.CDLL:
         L.lrsa_workspace_bytes.argtypes = [ctypes.c_void_p, ctypes.c_int]
         L.lrsa_num_scored_chunks.argtypes = [ctypes.c_void_p]
         L.lrsa_score_route.argtypes = [ctypes.c_void_p]
+        L.lrsa_score_poll_limit.argtypes = [ctypes.c_int]
+        L.lrsa_score_poll_limit.restype = ctypes.c_int
         vp, sz = ctypes.c_void_p, ctypes.c_size_t
         L.lrsa_score.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.lrsa_select.argtypes = [vp, vp, vp, vp, sz, vp]
@@ -114,8 +116,15 @@ def num_scored_chunks(p: LrsaParams) -> int:
 
 
 def score_route(p: LrsaParams) -> int:
-    """Which kernels score these params: 0 none, 1 one workgroup per chunk, 2 sliced, 3 streaming, 4 long chunks."""
+    """Which kernels score these params: 0 none, 1 one workgroup per chunk, 2 sliced, 3 one read (rows kept in
+    registers), 4 long chunks."""
     return _check(lib().lrsa_score_route(ctypes.byref(p)))
+
+
+def score_poll_limit(polls: int) -> int:
+    """Sets how often a one-read scoring workgroup polls for its hint words (negative: query only); returns the
+    previous value.  Results do not depend on it."""
+    return int(lib().lrsa_score_poll_limit(int(polls)))
 
 
 def workspace_bytes(p: LrsaParams, which: int) -> int:

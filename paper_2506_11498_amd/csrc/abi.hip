@@ -121,6 +121,8 @@ int lrsa_score_route(const lrsa_params* p) {
     return rc != LRSA_OK ? rc : lrsa::score_route(D);
 }
 
+int lrsa_score_poll_limit(int polls) { return lrsa::score_poll_limit(polls); }
+
 size_t lrsa_workspace_bytes(const lrsa_params* p, int which) {
     lrsa::Dims D;
     if (make_dims(p, &D) != LRSA_OK) return 0;

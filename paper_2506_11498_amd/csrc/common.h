@@ -41,9 +41,10 @@ int score_route(const Dims&);
 hipError_t launch_score(const Dims&, const void* K, const void* V, float* score, void* ws, hipStream_t st);
 
 hipError_t launch_softmax_select(const Dims&, const float* sigma, float* score, int32_t* idx, hipStream_t st);
-bool score_stream_applies(const Dims&);
-hipError_t launch_score_stream(const Dims&, const void* K, const void* V, float* score, int32_t* idx, float* sigma,
-                               hipStream_t st);
+bool score_resident_applies(const Dims&);
+int score_poll_limit(int polls);
+hipError_t launch_score_resident(const Dims&, const void* K, const void* V, float* score, int32_t* idx, float* sigma,
+                                 hipStream_t st);
 
 size_t select_ws_bytes(const Dims&);
 hipError_t launch_select(const Dims&, const float* score, int32_t* idx, void* ws, hipStream_t st);

@@ -11,7 +11,7 @@
 //   k_sigma           rows of chunk p normalised by the combined min / max, Std over channels
 //   k_softmax_select  Softmax over the L tokens of the chunk for K and for V, summed; optionally the top K
 // (chunks beyond 4096 tokens: k_softmax, then the stand-alone selection kernel).
-// Shapes with many (batch, KV head) streams go to the streaming kernel (score_stream.hip) instead.
+// bf16 data with head_dim 128 and chunks of 64 to 4096 rows go to the one-read kernel (score_resident.hip) instead.
 // All arithmetic is fp32 on the stored values with correctly rounded division and square root, two-pass
 // variance, max-subtracted softmax.  Rows are read with 16-byte loads, a row being spread over
 // consecutive lanes so that a wave reads whole rows back to back.
@@ -250,11 +250,12 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_score_fused(Dims D, const T* 
 //   2  sliced: one workgroup per (batch, KV head, chunk) would leave more than half of the CUs idle, and the
 //      chunks are long enough (1024 rows or more) that three launches over many workgroups beat one launch over
 //      few: measured at 60 units of 1024 rows, 8 + 11 + 9 us of kernel time against 43 us
-//   3  streaming: bf16, head_dim 128, enough (batch, KV head) streams to fill the chip: one read of K and V
+//   3  one read of K and V: bf16, head_dim 128, chunks of 64 to 4096 rows; a workgroup keeps its rows in registers
+//      from their min / max to their scores (score_resident.hip); taken whenever it applies
 //   4  chunks beyond the LDS of the one-workgroup kernel: sliced, with softmax and selection in launches of their own
 int score_route(const Dims& D) {
     if (D.Ns == 0) return 0;
-    if (score_stream_applies(D)) return 3;
+    if (score_resident_applies(D)) return 3;
     if (D.L > FUSED_MAX_L) return 4;
     return int64_t(D.Ns) * D.B * D.Hkv * 2 <= 256 && D.L >= 1024 ? 2 : 1;
 }
@@ -264,7 +265,7 @@ template <typename T>
 static hipError_t run_score(const Dims& D, const void* K, const void* V, float* score, int32_t* idx, void* ws,
                             hipStream_t st) {
     const int route = score_route(D);
-    if (route == 3) return launch_score_stream(D, K, V, score, idx, reinterpret_cast<float*>(ws), st);
+    if (route == 3) return launch_score_resident(D, K, V, score, idx, reinterpret_cast<float*>(ws), st);
     if (route == 1) {
         if (idx)
             LRSA_TIMED_LAUNCH("k_score_select_fused", st, (k_score_fused<T, true>), dim3(D.Ns, D.B * D.Hkv), dim3(FUSED_THREADS),

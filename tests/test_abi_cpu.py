@@ -105,9 +105,9 @@ def test_no_compressed_chunks_is_a_legal_noop_for_score_and_select():
 
 
 def test_scoring_route_of_the_workloads_and_of_edge_shapes():
-    """Host arithmetic: which kernels score a shape.  The streaming kernels need enough (batch, KV head, K or V)
-    streams to fill the chip with little read twice; few long chunks are cut into slices; the rest take one
-    workgroup per chunk."""
+    """Host arithmetic: which kernels score a shape.  bf16 data with head_dim 128 and chunks of 64 to 4096 rows go
+    to the one-read kernel; of the rest, few long chunks are cut into slices, chunks beyond 4096 rows take the long
+    path and everything else one workgroup per chunk."""
     import torch
     from paper_2506_11498_amd import inputs
 
@@ -116,18 +116,23 @@ def test_scoring_route_of_the_workloads_and_of_edge_shapes():
                              dtype=dtype, sink=S, lag=L, topk=K)
         return lrsa.score_route(p)
 
-    want = {"C1": 1, "C2": 1, "C3": 3, "C4": 1, "C5": 3, "C6": 2}
+    want = {"C1": 1, "C2": 3, "C3": 3, "C4": 3, "C5": 3, "C6": 3}
     for name, r in want.items():
         w = inputs.WORKLOADS[name]
         assert route(w.B, w.Hq, w.Hkv, w.d, w.n, w.L, w.K, w.S, w.torch_dtype) == r, name
     bf, f32 = torch.bfloat16, torch.float32
     assert route(1, 2, 2, 128, 16 + 2 * 64, 64, 8, 16, bf) == 0                    # nothing is ever seen compressed
     assert route(1, 1, 1, 128, 8 + 3 * 4100 + 9, 4100, 17, 8, bf) == 4             # chunk beyond 4096 tokens
-    assert route(1, 32, 32, 128, 16 + 16 * 512 + 100, 512, 100, 16, bf) == 3       # 64 streams x 2 ranges x 2 slices
-    assert route(1, 32, 32, 128, 16 + 16 * 512 + 100, 512, 100, 16, f32) == 1      # the streaming kernels are bf16 only
+    assert route(1, 32, 32, 128, 16 + 16 * 512 + 100, 512, 100, 16, bf) == 3       # 64 streams, two parts per chunk
+    assert route(1, 32, 32, 128, 16 + 16 * 512 + 100, 512, 100, 16, f32) == 1      # the one-read kernel is bf16 only
     assert route(1, 32, 32, 64, 16 + 16 * 512 + 100, 512, 100, 16, bf) == 1        # ... and head_dim 128 only
-    assert route(1, 2, 2, 128, 16 + 6 * 1024 + 100, 1024, 256, 16, bf) == 2        # 10 chunk units of 1024 rows
-    assert route(1, 2, 2, 128, 16 + 6 * 640 + 100, 640, 256, 16, bf) == 1          # few units, but short chunks
+    assert route(1, 2, 2, 128, 16 + 6 * 1024 + 100, 1024, 256, 16, bf) == 3
+    assert route(1, 2, 2, 128, 16 + 6 * 1024 + 100, 1024, 256, 16, f32) == 2       # 10 chunk units of 1024 rows
+    assert route(1, 2, 2, 128, 16 + 6 * 640 + 100, 640, 256, 16, f32) == 1         # few units, but short chunks
+    assert route(1, 2, 2, 128, 16 + 6 * 48 + 10, 48, 8, 16, bf) == 1               # chunks shorter than a wave of rows
+    assert route(1, 2, 2, 128, 8 + 3 * 4096 + 9, 4096, 17, 8, bf) == 3             # the longest chunk: sixteen parts
+    assert route(2, 80, 80, 128, 8 + 3 * 4096 + 9, 4096, 17, 8, bf) == 1           # 320 streams x 16 parts: too many
+                                                                                   # workgroups between writer and reader
 
 
 def test_product_package_does_not_import_the_oracle():

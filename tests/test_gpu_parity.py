@@ -183,24 +183,27 @@ def test_select_is_exact_on_heavily_tied_scores():
 # Which kernels score a shape is the library's choice; each case names the ones it is meant to exercise and the
 # test checks, through the library's kernel timers, that they are the ones that ran.
 ONE_WG = {"k_score_select_fused"}                             # one workgroup per (batch, KV head, chunk)
-SLICED = {"k_minmaxT", "k_sigmaT", "k_softmax_select"}        # few units of >= 1024 rows: cut into slices of 256 rows
+SLICED = {"k_minmaxT", "k_sigmaT", "k_softmax_select"}        # few units of >= 1024 rows: cut into slices of 128 rows
 LONG = {"k_minmaxT", "k_sigmaT", "k_softmax", "k_select"}     # chunks beyond 4096 tokens
+RESIDENT = {"k_score_resident", "k_softmax_select"}           # bf16, head_dim 128, chunks of 64 .. 4096 rows: one read
 
 
 @pytest.mark.parametrize("cfg", [
     dict(n=3 + 9 * 300 + 5, L=300, S=3, K=77, d=64, Hq=2, Hkv=2, B=2, dtype="f32", kernels=ONE_WG),       # ragged L, fp32
-    dict(n=16 + 6 * 640 + 100, L=640, S=16, K=256, d=128, Hq=2, Hkv=2, B=1, dtype="bf16", kernels=ONE_WG),
-    dict(n=16 + 6 * 1024 + 100, L=1024, S=16, K=256, d=128, Hq=2, Hkv=2, B=1, dtype="bf16", kernels=SLICED),
+    dict(n=16 + 6 * 640 + 100, L=640, S=16, K=256, d=64, Hq=2, Hkv=2, B=1, dtype="bf16", kernels=ONE_WG),
+    dict(n=16 + 6 * 640 + 100, L=640, S=16, K=256, d=128, Hq=2, Hkv=2, B=1, dtype="bf16", kernels=RESIDENT),
+    dict(n=16 + 6 * 1024 + 100, L=1024, S=16, K=256, d=128, Hq=2, Hkv=2, B=1, dtype="f32", kernels=SLICED),
+    dict(n=16 + 6 * 1024 + 100, L=1024, S=16, K=256, d=128, Hq=2, Hkv=2, B=1, dtype="bf16", kernels=RESIDENT),
     # one key per thread in the one-workgroup kernel; enough heads that it is the one chosen
-    dict(n=16 + 6 * 1024 + 100, L=1024, S=16, K=256, d=128, Hq=26, Hkv=26, B=1, dtype="bf16", kernels=ONE_WG),
+    dict(n=16 + 6 * 1024 + 100, L=1024, S=16, K=256, d=64, Hq=26, Hkv=26, B=1, dtype="bf16", kernels=ONE_WG),
     dict(n=5 + 4 * 2000 + 77, L=2000, S=5, K=100, d=64, Hq=2, Hkv=1, B=2, dtype="f32", kernels=SLICED),   # ragged last slice
-    dict(n=8 + 4 * 4096 + 9, L=4096, S=8, K=1000, d=128, Hq=1, Hkv=1, B=1, dtype="bf16", kernels=SLICED),
+    dict(n=8 + 4 * 4096 + 9, L=4096, S=8, K=1000, d=64, Hq=1, Hkv=1, B=1, dtype="bf16", kernels=SLICED),
     # largest chunk of the one-workgroup kernel (four rows per thread); enough heads that it is the one chosen
-    dict(n=8 + 5 * 4096 + 9, L=4096, S=8, K=1000, d=128, Hq=33, Hkv=33, B=1, dtype="bf16", kernels=ONE_WG),
+    dict(n=8 + 5 * 4096 + 9, L=4096, S=8, K=1000, d=64, Hq=33, Hkv=33, B=1, dtype="bf16", kernels=ONE_WG),
     dict(n=8 + 3 * 4100 + 9, L=4100, S=8, K=17, d=128, Hq=1, Hkv=1, B=1, dtype="bf16", kernels=LONG),
     dict(n=40, L=32, S=64, K=8, d=128, Hq=1, Hkv=1, B=1, dtype="bf16", kernels=set()),                    # nothing to score
-], ids=["f32_ragged", "bf16_L640", "bf16_L1024_sliced", "bf16_L1024_one_wg", "f32_L2000_sliced", "bf16_L4096_sliced", "bf16_L4096_one_wg",
-        "bf16_L4100_long", "no_chunks"])
+], ids=["f32_ragged", "bf16_d64_L640", "bf16_L640_resident", "f32_L1024_sliced", "bf16_L1024_resident", "bf16_d64_L1024_one_wg",
+        "f32_L2000_sliced", "bf16_d64_L4096_sliced", "bf16_d64_L4096_one_wg", "bf16_L4100_long", "no_chunks"])
 def test_fused_score_select_equals_the_two_calls_and_the_oracle(cfg):
     cfg = dict(cfg)
     kernels = cfg.pop("kernels")
