@@ -15,7 +15,7 @@ struct ScoreLds {
     float red[4][FUSED_THREADS / 64][128];   // per-wave partial min_K, max_K, min_V, max_V
     float s_mn[2][128], s_inv[2][128], s_den[2][128];
     float sig[2][FUSED_MAX_L];
-    float sm[FUSED_THREADS / 64];
+    float sm[2 * FUSED_THREADS / 64];
 };
 
 // Kcur / Vcur: row 0 of the chunk to score, Kref / Vref: row 0 of the chunk after it; `stride` elements
@@ -34,30 +34,34 @@ __device__ __forceinline__ float row16_sum(float v) {
 
 // Eq. 7-8 given the standard deviations: max-subtracted softmax of sig0 over the L tokens, the same for sig1,
 // their sum written to sig0[r] (and to out[r] when out is not null).  sig0, sig1: LDS, L floats each, complete
-// and visible to the NT threads of the block on entry; sm: NT/64 floats of LDS.  Each thread touches only rows
+// and visible to the NT threads of the block on entry; sm: 2 * NT/64 floats of LDS.  Each thread touches only rows
 // r = tid, tid + NT, ...: callers that read other rows afterwards synchronise first.
 template <int NT>
 __device__ __forceinline__ void softmax_sum_block(float* sig0, const float* sig1, float* sm, int L,
                                                   float* __restrict__ out) {
     constexpr int NW = NT / 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    auto block_red = [&](float v, bool is_max) {
-        v = is_max ? wave_max(v) : wave_sum(v);
+    // the K and the V value reduced over the block together (one pair of barriers for both)
+    auto block_red2 = [&](float& a, float& b, bool is_max) {
+        a = is_max ? wave_max(a) : wave_sum(a);
+        b = is_max ? wave_max(b) : wave_sum(b);
         __syncthreads();
-        if (lane == 0) sm[wave] = v;
+        if (lane == 0) { sm[wave] = a; sm[NW + wave] = b; }
         __syncthreads();
-        float r = sm[0];
-        for (int i = 1; i < NW; ++i) r = is_max ? fmaxf(r, sm[i]) : r + sm[i];
-        return r;
+        float ra = sm[0], rb = sm[NW];
+        for (int i = 1; i < NW; ++i) {
+            ra = is_max ? fmaxf(ra, sm[i]) : ra + sm[i];
+            rb = is_max ? fmaxf(rb, sm[NW + i]) : rb + sm[NW + i];
+        }
+        a = ra;
+        b = rb;
     };
     float mk = -INFINITY, mv = -INFINITY;
     for (int r = tid; r < L; r += NT) { mk = fmaxf(mk, sig0[r]); mv = fmaxf(mv, sig1[r]); }
-    mk = block_red(mk, true);
-    mv = block_red(mv, true);
+    block_red2(mk, mv, true);
     float zk = 0.0f, zv = 0.0f;
     for (int r = tid; r < L; r += NT) { zk += expf(sig0[r] - mk); zv += expf(sig1[r] - mv); }
-    zk = block_red(zk, false);
-    zv = block_red(zv, false);
+    block_red2(zk, zv, false);
     for (int r = tid; r < L; r += NT) {
         const float sc = expf(sig0[r] - mk) / zk + expf(sig1[r] - mv) / zv;
         if (out) out[r] = sc;

@@ -393,7 +393,7 @@ __global__ __launch_bounds__(NT) void k_softmax_select(Dims D, const float* __re
                                                        int32_t* __restrict__ idx, mail_t* mail, int mail_words) {
     const int p = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
     extern __shared__ float sx_sig[];     // [2][L]
-    __shared__ float sm[NT / 64];
+    __shared__ float sm[2 * NT / 64];
     float* sig0 = sx_sig;
     float* sig1 = sx_sig + D.L;
     const float* sk = sigma + ((int64_t(bh) * 2 + 0) * D.Ns + p) * D.L;

@@ -8,8 +8,10 @@
 // digits are taken from (pattern - smallest pattern of the chunk), shifted left until the span's top bit is
 // bit 31: the first histogram then spreads over the buckets instead of piling its LDS atomics on one or two
 // addresses, and a narrow span needs fewer than four passes.  The map is monotone and one-to-one, so the
-// order, the ties and hence the selection are unchanged.  All integer work, hence deterministic.  Used by
-// the stand-alone selection kernel (keys in global memory) and by the scoring kernels (keys in LDS).
+// order, the ties and hence the selection are unchanged.  The passes stop as soon as the bucket that holds the
+// K-th largest element is wanted whole (after two bytes it usually holds that element alone): the bytes below
+// would only order elements that are all taken.  All integer work, hence deterministic.  Used by the
+// stand-alone selection kernel (keys in global memory) and by the scoring kernels (keys in LDS).
 #pragma once
 #include "common.h"
 
@@ -20,6 +22,7 @@ struct SelectLds {
     int sm[16];
     uint32_t prefix;
     int need;
+    int all;      // every element of the chosen bucket is wanted: the lower bytes decide nothing
 };
 
 // exclusive prefix sum of `v` over the NT threads of the block; *total receives the block sum
@@ -107,6 +110,7 @@ __device__ __forceinline__ void select_topk_block(const uint32_t* key, int L, in
                 if (above < need && need <= above + c[i]) {
                     sh.prefix = prefix | (uint32_t(255 - 4 * lane - i) << shift);
                     sh.need = need - above;
+                    sh.all = need - above == c[i] ? 1 : 0;
                 }
                 above += c[i];
             }
@@ -115,19 +119,35 @@ __device__ __forceinline__ void select_topk_block(const uint32_t* key, int L, in
         prefix = sh.prefix;
         need = sh.need;
         mask |= 0xffu << shift;
+        if (sh.all) break;
     }
-    // prefix is now the K-th largest (shifted) pattern; `need` of the elements equal to it are taken.  One packed
-    // scan per NT elements: larger ones in the low half-word, equal ones in the high half-word.
+    // On the decided bytes (`mask`), `prefix` is the pattern of the K-th largest element; `need` of the elements
+    // that equal it there are taken, the first ones in position order (all of them after an early stop).  Every
+    // thread takes SEL_RUN consecutive positions, so that one packed scan serves SEL_RUN * NT elements: larger
+    // ones in the low half-word, equal ones in the high half-word.
+    constexpr int SEL_RUN = 4;
     int gt_seen = 0, eq_seen = 0;
-    for (int r0 = 0; r0 < L; r0 += NT) {
-        const int r = r0 + tid;
-        const uint32_t k = r < L ? rel(key[r]) : 0u;
-        const int is_gt = (r < L && k > prefix) ? 1 : 0;
-        const int is_eq = (r < L && k == prefix) ? 1 : 0;
+    for (int b0 = 0; b0 < L; b0 += SEL_RUN * NT) {
+        const int r0 = b0 + tid * SEL_RUN;
+        uint32_t km[SEL_RUN];
+        int ngt = 0, neq = 0;
+#pragma unroll
+        for (int i = 0; i < SEL_RUN; ++i) {
+            km[i] = r0 + i < L ? rel(key[r0 + i]) & mask : 0u;
+            ngt += (r0 + i < L && km[i] > prefix) ? 1 : 0;
+            neq += (r0 + i < L && km[i] == prefix) ? 1 : 0;
+        }
         int total;
-        const int before = block_exscan<NT>(is_gt | (is_eq << 16), sh.sm, &total);
-        const int gt_before = gt_seen + (before & 0xffff), eq_before = eq_seen + (before >> 16);
-        if (is_gt || (is_eq && eq_before < need)) out[gt_before + min(eq_before, need)] = base + r;
+        const int before = block_exscan<NT>(ngt | (neq << 16), sh.sm, &total);
+        int g = gt_seen + (before & 0xffff), e = eq_seen + (before >> 16);
+#pragma unroll
+        for (int i = 0; i < SEL_RUN; ++i) {
+            if (r0 + i >= L) break;
+            const bool is_gt = km[i] > prefix, is_eq = km[i] == prefix;
+            if (is_gt || (is_eq && e < need)) out[g + min(e, need)] = base + r0 + i;
+            g += is_gt ? 1 : 0;
+            e += is_eq ? 1 : 0;
+        }
         gt_seen += total & 0xffff;
         eq_seen += total >> 16;
     }
