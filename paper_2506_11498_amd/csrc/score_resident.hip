@@ -30,7 +30,6 @@
 // the channels is sum(x^2) - sum(x)^2 / d in fp32 and is recomputed from the deviations for a row in which the two
 // terms cancel.  Values of magnitude >= 2^121 or NaN are outside the contract (their bf16 patterns do not order
 // like numbers in a 16-bit float compare).
-#include "mfma_tiles.h"
 #include "score_block.h"
 #include "select_block.h"
 

@@ -154,3 +154,37 @@ def test_rows_whose_normalised_channels_are_nearly_equal():
     same[0, 1, 2] = False
     same[0, 1, 1] = False
     assert torch.equal(score[same], score_plain[same])
+
+
+def test_calls_that_overlap_on_two_streams_cost_time_never_results():
+    """Two calls that score at the same time share the library's mailbox slots: each may overwrite or clear the
+    words the other is waiting for.  A reader that does not find its tags takes the min / max from the rows, so
+    both calls must still give the bits they give alone.  (Different shapes, so that the slots of one call mean
+    other streams, chunks and parts to the other.)"""
+    cfg_a = dict(n=16 + 16 * 512 + 100, L=512, S=16, K=100, d=128, Hq=32, Hkv=32, B=1, dtype="bf16")
+    cfg_b = dict(n=7 + 23 * 200 + 100, L=200, S=7, K=50, d=128, Hq=16, Hkv=16, B=2, dtype="bf16")
+    wa, wb = inputs.small_workload(**cfg_a), inputs.small_workload(seed=5, **cfg_b)
+    xa, xb = inputs.make_inputs(wa), inputs.make_inputs(wb)
+    da = {k: xa[k].to(DEV) for k in ("Q", "K", "V")}
+    db = {k: xb[k].to(DEV) for k in ("Q", "K", "V")}
+    pa = lrsa.params_for(da["Q"], da["K"], sink=wa.S, lag=wa.L, topk=wa.K)
+    pb = lrsa.params_for(db["Q"], db["K"], sink=wb.S, lag=wb.L, topk=wb.K)
+    sa0, ia0 = lrsa.lrsa_score_select(pa, da["K"], da["V"])
+    sb0, ib0 = lrsa.lrsa_score_select(pb, db["K"], db["V"])
+    torch.cuda.synchronize()
+    before = lrsa.score_poll_limit(64)      # a lost word is given up after 64 polls: keeps the test short
+    try:
+        st_a, st_b = torch.cuda.Stream(), torch.cuda.Stream()
+        outs_a, outs_b = [], []
+        for _ in range(8):
+            with torch.cuda.stream(st_a):
+                outs_a.append(lrsa.lrsa_score_select(pa, da["K"], da["V"]))
+            with torch.cuda.stream(st_b):
+                outs_b.append(lrsa.lrsa_score_select(pb, db["K"], db["V"]))
+        torch.cuda.synchronize()
+    finally:
+        lrsa.score_poll_limit(before)
+    for s_, i_ in outs_a:
+        assert torch.equal(s_, sa0) and torch.equal(i_, ia0)
+    for s_, i_ in outs_b:
+        assert torch.equal(s_, sb0) and torch.equal(i_, ib0)
