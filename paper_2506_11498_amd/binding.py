@@ -225,7 +225,8 @@ def lrsa_check_idx(p: LrsaParams, idx: Optional[torch.Tensor], bad_rows: Optiona
 
 def lrsa_score_select(p: LrsaParams, K: torch.Tensor, V: torch.Tensor, score: Optional[torch.Tensor] = None,
                       idx: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
-    """lrsa_score and lrsa_select in one call (one launch where the fused kernel applies): (score, idx)."""
+    """lrsa_score and lrsa_select in one call (the selection is taken by the kernel that finishes the scores):
+    (score, idx)."""
     Ns = num_scored_chunks(p)
     if score is None:
         score = torch.empty((p.batch, p.heads_kv, Ns, p.lag), dtype=torch.float32, device=K.device)

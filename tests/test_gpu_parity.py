@@ -299,7 +299,7 @@ def full_workload_parity(name, kv_heads, batch=0, n_rows=None, n_cols=None, seed
     Kf, Vf = x["K"].float().numpy(), x["V"].float().numpy()
     sc_ref = ref.score(Kf, Vf, w.S, w.L)
     idx_ref = ref.select(sc_ref, w.S, w.L, w.K)
-    # the calls as bench.py makes them: one launch for score + select, preallocated outputs, one workspace
+    # the calls as bench.py makes them: one call for score + select, preallocated outputs, one workspace
     # of the largest size shared by all calls
     p = params(w, xd, impl=impl)
     Ns = lrsa.num_scored_chunks(p)
