@@ -52,7 +52,8 @@ static double dot(const float *a, const float *b, int d)
 /* Forward (and dQ) for the listed query rows.
  * Outputs, indexed [g][r] over the G heads and the nrows listed rows:
  *   O [G][nrows][d], lse [G][nrows]; when dO != NULL also D = rowsum(dO*O) [G][nrows]
- *   and dQ [G][nrows][d] = scale * sum_u dS[t,u] k_u with dS = A (dA - D).
+ *   and, unless dQ is NULL (a caller that wants lse and D only), dQ [G][nrows][d] =
+ *   scale * sum_u dS[t,u] k_u with dS = A (dA - D).
  * Returns 0, or -1 when memory runs out. */
 int lrsa_oracle_rows(const lrsa_oracle_cfg *c, const float *Q, const float *K, const float *V,
                      const float *dO, const int32_t *idx, const int64_t *rows, int64_t nrows,
@@ -104,6 +105,7 @@ int lrsa_oracle_rows(const lrsa_oracle_cfg *c, const float *Q, const float *K, c
                         double Dt = 0.0;
                         for (int x = 0; x < d; ++x) Dt += (double)go[x] * o[x];
                         D[(int64_t)g * nrows + r] = Dt;
+                        if (!dQ) continue;
                         double *dq = dQ + ((int64_t)g * nrows + r) * d;
                         for (int x = 0; x < d; ++x) dq[x] = 0.0;
                         for (int64_t j = 0; j < m; ++j) {

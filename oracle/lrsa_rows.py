@@ -58,9 +58,9 @@ def _cfg(Q, S, L, K, idx, local_prev, scale):
 
 
 def attn_rows(Q, K, V, dO, idx, rows: Sequence[int], S: int, L: int, topk: int,
-              local_prev: int = 1, scale=None) -> dict:
-    """O, lse (and D, dQ when dO is given) of the listed rows for one KV group.
-    Q, dO: [G, n, d]; K, V: [n, d]; idx: [Ns, K] or None."""
+              local_prev: int = 1, scale=None, want_dq: bool = True) -> dict:
+    """O, lse (and D, dQ when dO is given; want_dq=False leaves dQ out, which halves the time) of the listed
+    rows for one KV group.  Q, dO: [G, n, d]; K, V: [n, d]; idx: [Ns, K] or None."""
     lib = _load()
     Q, K, V, dO = _f32(Q), _f32(K), _f32(V), _f32(dO)
     idx = None if idx is None or idx.size == 0 else np.ascontiguousarray(idx, dtype=np.int32)
@@ -70,7 +70,8 @@ def attn_rows(Q, K, V, dO, idx, rows: Sequence[int], S: int, L: int, topk: int,
     out = {"O": np.empty((G, len(rows), d)), "lse": np.empty((G, len(rows)))}
     if dO is not None:
         out["D"] = np.empty((G, len(rows)))
-        out["dQ"] = np.empty((G, len(rows), d))
+        if want_dq:
+            out["dQ"] = np.empty((G, len(rows), d))
     rc = lib.lrsa_oracle_rows(ctypes.byref(cfg), _p(Q), _p(K), _p(V), _p(dO), _p(idx), _p(rows),
                               ctypes.c_int64(len(rows)), _p(out["O"]), _p(out["lse"]),
                               _p(out.get("D")), _p(out.get("dQ")))

@@ -345,15 +345,14 @@ def full_workload_parity(name, kv_heads, batch=0, n_rows=None, n_cols=None, seed
         # row), piece by piece; O and dQ are kept for the sampled rows
         need = np.union1d(rsel, rows.rows_seeing(csel, w.n, w.S, w.L, idx_ref[batch, h]))
         lse_all, D_all = np.full((G, w.n), np.nan), np.full((G, w.n), np.nan)
-        r = {"O": np.empty((G, len(rsel), w.d)), "dQ": np.empty((G, len(rsel), w.d)), "lse": np.empty((G, len(rsel)))}
-        for i0 in range(0, len(need), 8192):
-            piece = need[i0:i0 + 8192]
-            rp = rows.attn_rows(*args, piece, w.S, w.L, w.K)
+        r = rows.attn_rows(*args, rsel, w.S, w.L, w.K)                      # O, lse, D, dQ of the sampled rows
+        lse_all[:, rsel], D_all[:, rsel] = r["lse"], r["D"]
+        rest = np.setdiff1d(need, rsel)                                     # the other rows: lse and D only
+        for i0 in range(0, len(rest), 8192):
+            piece = rest[i0:i0 + 8192]
+            rp = rows.attn_rows(*args, piece, w.S, w.L, w.K, want_dq=False)
             lse_all[:, piece], D_all[:, piece] = rp["lse"], rp["D"]
-            keep = np.isin(piece, rsel)
-            at = np.searchsorted(rsel, piece[keep])
-            r["O"][:, at], r["dQ"][:, at], r["lse"][:, at] = rp["O"][:, keep], rp["dQ"][:, keep], rp["lse"][:, keep]
-            progress(f"{name} KV head {h}: oracle rows {i0 + len(piece)}/{len(need)}")
+            progress(f"{name} KV head {h}: oracle rows {len(rsel) + i0 + len(piece)}/{len(need)}")
         r.update(rows.attn_cols(*args, csel, w.S, w.L, w.K, lse_all=lse_all, D_all=D_all))
         progress(f"{name} KV head {h}: oracle columns {len(csel)}")
         assert_close(f"O[h{h}]", to_np(O[batch, sl][:, rsel]), r["O"], t)

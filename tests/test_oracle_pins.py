@@ -423,6 +423,10 @@ def test_rowwise_c_oracle_equals_dense_oracle(cfg):
     r = rows.attn_rows(x["Q"][0, :G], x["K"][0, 0], x["V"][0, 0], x["dO"][0, :G],
                        None if idx is None else idx[0, 0], pick, w.S, w.L, w.K)
     assert np.allclose(r["O"], O[0, :G][:, pick], rtol=1e-11, atol=1e-13)
+    # a caller that wants lse and D only gets the same O, lse and D, and no dQ
+    r2 = rows.attn_rows(x["Q"][0, :G], x["K"][0, 0], x["V"][0, 0], x["dO"][0, :G],
+                        None if idx is None else idx[0, 0], pick, w.S, w.L, w.K, want_dq=False)
+    assert "dQ" not in r2 and all(np.array_equal(r2[k], r[k]) for k in ("O", "lse", "D"))
     c = rows.attn_cols(x["Q"][0, :G], x["K"][0, 0], x["V"][0, 0], x["dO"][0, :G],
                        None if idx is None else idx[0, 0], pick, w.S, w.L, w.K)
     assert np.allclose(c["dK"], dK[0, 0][pick], rtol=1e-10, atol=1e-13)
