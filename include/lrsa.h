@@ -95,10 +95,10 @@ int lrsa_score_route(const lrsa_params *p);
 
 /* On route 3 a scoring workgroup takes the min / max of its reference chunk (Eq. 4-5) from hint words that
  * the workgroups of that chunk publish; `polls` is how many times it looks for them before it computes
- * these min / max from the rows themselves (a second read of the chunk).  Default 4096; 0: never wait (every
- * chunk is read twice).  Scores and selections are the same bits for every value: the setting trades time
- * only.  Process-wide, takes effect with the next call; negative: change nothing.  Returns the previous
- * value. */
+ * these min / max from the rows themselves (a second read of the chunk).  Default 256 (about a
+ * millisecond); 0: never wait (every chunk is read twice).  Scores and selections are the same bits for
+ * every value: the setting trades time only.  Process-wide, takes effect with the next call; negative:
+ * change nothing.  Returns the previous value. */
 int lrsa_score_poll_limit(int polls);
 
 /* Bytes of device scratch the call `which` (lrsa_ws_kind) needs for these params; host arithmetic.

@@ -17,7 +17,7 @@
 //   * a workgroup publishes the 128 words of its part into the slot `its index in the grid modulo SR_MAIL_SLOTS`.
 //     A reader and its writers are nstreams * W (+- W) workgroups apart; two workgroups that share a slot are
 //     SR_MAIL_SLOTS apart and, the plan sees to it, belong to different chunks, so their tags differ;
-//   * the mailboxes are hints only: a reader that does not find its tags within SR_SPIN polls computes the min / max
+//   * the mailboxes are hints only: a reader that does not find its tags within its poll limit computes the min / max
 //     of the reference chunk from the rows themselves.  Whatever the mailboxes hold, results are the same.
 // Several small workgroups share a CU: the loads of a CU return in the order they were issued, so the first
 // workgroup scores while the data of the next ones is still arriving.
@@ -39,7 +39,9 @@
 namespace lrsa {
 
 constexpr int SR_MAX_PARTS = 16;     // parts per chunk: the bits of a reader's "have" mask
-constexpr int SR_SPIN = 4096;        // polls before a reader stops waiting for a mailbox (the default of lrsa_score_poll_limit)
+constexpr int SR_SPIN = 256;         // polls before a reader stops waiting for a mailbox (the default of lrsa_score_poll_limit):
+                                     // a writer's words are usually there at the first or second look; 256 looks are about a
+                                     // millisecond, after which a second read of the chunk is the cheaper way
 constexpr int SR_MAX_CHUNKS = 4095;  // the chunk index is 12 bits of the tag
 constexpr int SR_MAIL_SLOTS = 8192;  // slots of 128 words (8 MB)
 

@@ -117,7 +117,7 @@ def test_without_the_hint_words_every_workgroup_reads_its_reference_chunk_and_ge
             (score, idx), names = kernels_of(lambda: lrsa.lrsa_score_select(p, xd["K"], xd["V"]))
         finally:
             lrsa.score_poll_limit(before)
-        assert lrsa.score_poll_limit(-1) == before == 4096
+        assert lrsa.score_poll_limit(-1) == before == 256
         assert "k_score_resident" in names
         assert torch.equal(score, score0) and torch.equal(idx, idx0)
 
