@@ -33,6 +33,9 @@ RESIDENT = [
     dict(name="batch_overlap", n=7 + 23 * 200 + 100, L=200, S=7, K=50, d=128, Hq=16, Hkv=16, B=2, dtype="bf16"),
     # the longest chunk the kernel takes: sixteen parts, a reader polls in four rounds of four
     dict(name="sixteen_parts", n=8 + 4 * 4096 + 9, L=4096, S=8, K=1000, d=128, Hq=1, Hkv=1, B=1, dtype="bf16"),
+    # every token of a chunk kept (the selection stops after its first pass) and a single one kept
+    dict(name="keep_all", n=9 + 6 * 256 + 30, L=256, S=9, K=256, d=128, Hq=4, Hkv=2, B=1, dtype="bf16"),
+    dict(name="keep_one", n=9 + 6 * 256 + 30, L=256, S=9, K=1, d=128, Hq=4, Hkv=2, B=1, dtype="bf16"),
     # more workgroups than mailbox slots (4 * 2 * 1041 = 8328 > 8192): the slots wrap around
     dict(name="slots_wrap", n=4 + 1041 * 64 + 7, L=64, S=4, K=8, d=128, Hq=4, Hkv=4, B=1, dtype="bf16"),
 ]
