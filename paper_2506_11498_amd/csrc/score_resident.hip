@@ -416,11 +416,22 @@ static hipError_t run_softmax_select(const Dims& D, const float* sigma, float* s
                                      int mail_words, hipStream_t st) {
     const size_t lds = size_t(2) * D.L * sizeof(float);
     const dim3 grid(D.Ns, D.B * D.Hkv);
-    const bool few = int64_t(D.Ns) * D.B * D.Hkv <= 128 && D.L >= 1024;
+    // threads per chunk (measured): chunks of 1024 rows and more take 1024 threads when there are at most half as many
+    // chunks as CUs and 512 when at most two per CU (C4: 12.4 -> 11.3 us, C5: 22.9 -> 18.9 us against 256 threads);
+    // shorter or more chunks take 256 (C3, 992 chunks of 512 rows: 13.3 us against 15.7 us with 512)
+    const int64_t chunks = int64_t(D.Ns) * D.B * D.Hkv;
+    const int nt = D.L >= 1024 && chunks <= 128 ? 1024 : D.L >= 1024 && chunks <= 512 ? 512 : 256;
 #define LRSA_SX(name, SEL, NT_) \
     LRSA_TIMED_LAUNCH(name, st, (k_softmax_select<SEL, NT_>), grid, dim3(NT_), lds, st, D, sigma, score, idx, mail, mail_words)
-    if (idx) { if (few) LRSA_SX("k_softmax_select", true, 1024); else LRSA_SX("k_softmax_select", true, 256); }
-    else { if (few) LRSA_SX("k_softmax", false, 1024); else LRSA_SX("k_softmax", false, 256); }
+    if (idx) {
+        if (nt == 1024) LRSA_SX("k_softmax_select", true, 1024);
+        else if (nt == 512) LRSA_SX("k_softmax_select", true, 512);
+        else LRSA_SX("k_softmax_select", true, 256);
+    } else {
+        if (nt == 1024) LRSA_SX("k_softmax", false, 1024);
+        else if (nt == 512) LRSA_SX("k_softmax", false, 512);
+        else LRSA_SX("k_softmax", false, 256);
+    }
 #undef LRSA_SX
     return hipGetLastError();
 }
