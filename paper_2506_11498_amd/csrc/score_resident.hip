@@ -387,34 +387,81 @@ static ResidentPlan make_resident_plan(const Dims& D) {
 // Softmax over the chunk's tokens for K and V, summed (Eq. 7-8); SELECT: the chunk's top K right away (text after
 // Eq. 8).  One workgroup of NT threads per (batch, KV head, chunk).  The work is a chain of short block-wide
 // reductions and scans: with many chunks small workgroups (several per CU) finish soonest, with few chunks (fewer
-// than CUs) the chain itself is the time and more threads shorten it.  Dynamic LDS: 2 * L floats.  The workgroups
-// also clear the mailbox words that the scoring kernel of this call may have written.
+// than CUs) the chain itself is the time and more threads shorten it.  A thread keeps its rows in registers from the
+// load to the score; dynamic LDS: L floats (the scores, for the selection).  The workgroups also clear the mailbox
+// words that the scoring kernel of this call may have written.
 template <bool SELECT, int NT>
 __global__ __launch_bounds__(NT) void k_softmax_select(Dims D, const float* __restrict__ sigma, float* __restrict__ score,
                                                        int32_t* __restrict__ idx, mail_t* mail, int mail_words) {
-    const int p = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
-    extern __shared__ float sx_sig[];     // [2][L]
-    __shared__ float sm[2 * NT / 64];
-    float* sig0 = sx_sig;
-    float* sig1 = sx_sig + D.L;
+    constexpr int NW = NT / 64, MAXJ = FUSED_MAX_L / NT;   // rows tid, tid + NT, ... of a thread: at most MAXJ
+    const int p = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    extern __shared__ float sx_key[];     // [L]: the scores, for the selection
+    __shared__ float sm[2 * NW];
+    // the mailbox words first: the stores drain while the standard deviations are on their way
+    const int64_t g = int64_t(bh) * gridDim.x + p, G = int64_t(gridDim.x) * gridDim.y;
+    for (int64_t e = g * NT + tid; e < mail_words; e += G * NT) mail[e] = 0;
     const float* sk = sigma + ((int64_t(bh) * 2 + 0) * D.Ns + p) * D.L;
     const float* sv = sigma + ((int64_t(bh) * 2 + 1) * D.Ns + p) * D.L;
-    for (int r = tid; r < D.L; r += NT) { sig0[r] = sk[r]; sig1[r] = sv[r]; }
-    __syncthreads();
-    softmax_sum_block<NT>(sig0, sig1, sm, D.L, score + (int64_t(bh) * D.Ns + p) * D.L);
+    // The thread's rows stay in registers; a row past the chunk counts as -inf (its exponential is 0).
+    float vk[MAXJ], vv[MAXJ];
+#pragma unroll
+    for (int j = 0; j < MAXJ; ++j) {
+        const int r = tid + j * NT;
+        const bool in = j * NT < D.L && r < D.L;
+        vk[j] = in ? sk[r] : -INFINITY;
+        vv[j] = in ? sv[r] : -INFINITY;
+    }
+    // the K and the V value reduced over the block together (one pair of barriers for both)
+    auto block_red2 = [&](float& a, float& b, bool is_max) {
+        a = is_max ? wave_max(a) : wave_sum(a);
+        b = is_max ? wave_max(b) : wave_sum(b);
+        __syncthreads();
+        if (lane == 0) { sm[wave] = a; sm[NW + wave] = b; }
+        __syncthreads();
+        float ra = sm[0], rb = sm[NW];
+        for (int i = 1; i < NW; ++i) {
+            ra = is_max ? fmaxf(ra, sm[i]) : ra + sm[i];
+            rb = is_max ? fmaxf(rb, sm[NW + i]) : rb + sm[NW + i];
+        }
+        a = ra;
+        b = rb;
+    };
+    float mk = -INFINITY, mv = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < MAXJ; ++j) { mk = fmaxf(mk, vk[j]); mv = fmaxf(mv, vv[j]); }
+    block_red2(mk, mv, true);
+    float zk = 0.0f, zv = 0.0f;
+#pragma unroll
+    for (int j = 0; j < MAXJ; ++j) {
+        if (j * NT < D.L) {
+            vk[j] = expf(vk[j] - mk);
+            vv[j] = expf(vv[j] - mv);
+            zk += vk[j];
+            zv += vv[j];
+        }
+    }
+    block_red2(zk, zv, false);
+    float* out = score + (int64_t(bh) * D.Ns + p) * D.L;
+#pragma unroll
+    for (int j = 0; j < MAXJ; ++j) {
+        const int r = tid + j * NT;
+        if (j * NT < D.L && r < D.L) {
+            const float sc = vk[j] / zk + vv[j] / zv;      // Eq. 7-8
+            out[r] = sc;
+            if (SELECT) sx_key[r] = sc;
+        }
+    }
     if (SELECT) {
         __shared__ SelectLds sel;
         __syncthreads();
-        select_topk_block<NT>(reinterpret_cast<const uint32_t*>(sig0), D.L, D.K, D.S + p * D.L,
+        select_topk_block<NT>(reinterpret_cast<const uint32_t*>(sx_key), D.L, D.K, D.S + p * D.L,
                               idx + (int64_t(bh) * D.Ns + p) * D.K, sel);
     }
-    const int64_t g = int64_t(bh) * gridDim.x + p, G = int64_t(gridDim.x) * gridDim.y;
-    for (int64_t e = g * NT + tid; e < mail_words; e += G * NT) mail[e] = 0;
 }
 
 static hipError_t run_softmax_select(const Dims& D, const float* sigma, float* score, int32_t* idx, mail_t* mail,
                                      int mail_words, hipStream_t st) {
-    const size_t lds = size_t(2) * D.L * sizeof(float);
+    const size_t lds = size_t(D.L) * sizeof(float);
     const dim3 grid(D.Ns, D.B * D.Hkv);
     // threads per chunk (measured): chunks of 1024 rows and more take 1024 threads when there are at most half as many
     // chunks as CUs and 512 when at most two per CU (C4: 12.4 -> 11.3 us, C5: 22.9 -> 18.9 us against 256 threads);
